@@ -104,6 +104,14 @@ def _time_steps(fn, steps, warmup):
     return wall, e0.elapsed_time(e1) * 1e-3
 
 
+def _lstm_completed(ws, h):
+    import torch
+    torch.cuda.synchronize()
+    gave_up = int(ws[:8].view(torch.int32)[1].item())
+    if gave_up or not bool(torch.isfinite(h).all().item()):
+        raise RuntimeError("bench.py: the resident LSTM kernel gave up at its step barrier; the timing is void")
+
+
 # ------------------------------------------------------------------ workloads ----
 def make_cfg1():
     import torch
@@ -192,8 +200,10 @@ def make_cfg4():
     h, s = torch.empty((50, 64, 1024), device="cuda"), torch.empty((50, 64, 1024), device="cuda")
     g = torch.empty((4, 50, 64, 1024), device="cuda")
     desc = brg.LstmDesc(50, 64, 1024, 1024, 16, 64, 64)
-    ws = torch.zeros(64, dtype=torch.uint8, device="cuda")   # grid-barrier words of the persistent kernel
+    ws = torch.zeros(64, dtype=torch.uint8, device="cuda")   # grid-barrier words of the resident kernel
     fn = lambda: brg.brg_lstm_fwd(desc, brg.F32, dx, dW, dR, None, None, None, h, s, g, ws)
+    # after the timed region: the resident kernel reports a barrier time-out through word 1 (and NaN-fills its outputs)
+    fn.verify = lambda: _lstm_completed(ws, h)
     return fn, 50 * 2.0 * 64 * 4 * 1024 * 2048, "f32", "cfg4: LSTM fwd T=50 N=64 C=K=1024, fp32"
 
 
@@ -372,6 +382,8 @@ def main():
 
     fn, flops, dt, name = MAKERS[args.workload](args.batch) if args.batch else MAKERS[args.workload]()
     wall, dev_s = _time_steps(fn, args.steps, args.warmup)
+    if hasattr(fn, "verify"):
+        fn.verify()
     per_step = wall / args.steps
     gflops = flops / per_step / 1e9
     kern_tflops = flops / (dev_s / args.steps) / 1e12
@@ -395,6 +407,8 @@ def main():
             f2, fl2, dt2, nm2 = MAKERS[key]()
             st, wu = (30, 5) if key in ("cfg4", "cfg4_bwd") else (100, 10)
             _, d2 = _time_steps(f2, st, wu)
+            if hasattr(f2, "verify"):
+                f2.verify()
             t = d2 / st
             others[key] = {"workload": nm2, "us_per_step": round(t * 1e6, 2), "gflops": round(fl2 / t / 1e9, 1),
                            "pct_of_mfma_peak": round(100 * fl2 / t / 1e12 / PEAK_TFLOPS[dt2], 2)}

@@ -53,6 +53,31 @@ const char *brg_last_error(void);
 /* Library version string, HOST pointer. */
 const char *brg_version(void);
 
+/* Tuning overrides -- NOT part of the ABI contract.  A set of environment variables forces a kernel variant
+ * the planner would not choose by itself; they exist so that every variant can be parity-tested and timed.
+ * The environment is read once, at the first call into the library; brg_tuning_reload() reads it again
+ * (not safe against calls running at the same time on other threads).  Results never depend on them
+ * beyond rounding order.  Presence alone switches the ones marked (flag); the others take a number.
+ *   BRG_GEMM_GENERAL (flag)   brg_gemm*: always the general tile kernel
+ *   BRG_NO_RING (flag)        64-cubed fp32 blocks: the double-buffered kernel instead of the four-stage ring
+ *   BRG_FC_GENERAL (flag), BRG_FC_WGT_GENERAL (flag), BRG_FC_G64 = 64|32, BRG_FC_G128 = 0|1
+ *                             fully connected layers: general kernel / tile shape of the tuned ones
+ *   BRG_LSTM_GENERAL (flag)   LSTM forward and backward: one general launch per time step
+ *   BRG_CONV_GENERAL (flag), BRG_CONV_NO1X1 (flag), BRG_CONV_WGT_GENERAL (flag)
+ *                             convolutions: general kernel for all / for 1x1 layers / for the weight gradient
+ *   BRG_CONV_KW = 1|2, BRG_CONV_PITCH = 0, BRG_CONV_ZEROFILL (flag), BRG_CONV_NOFUSE (flag)
+ *                             tiled bf16 kernel: feature blocks per wave, halo pitch rule, separate zero fill and
+ *                             unfused parity classes of the strided backward pass
+ *   BRG_CONV_1X1_KW = 1|2|4, BRG_CONV_1X1_PG = 2|4, BRG_CONV_1X1_WF = 1|2|4, BRG_CONV_1X1_SPLIT = 0|1,
+ *   BRG_CONV_1X1_LDS = 0|1, BRG_CONV_1X1_LDS_NGW = 2|4, BRG_CONV_1X1_LDS_PM = 0|1
+ *                             bf16 1x1 layers: wave tile of the streaming kernel, split-reduction and
+ *                             workgroup-tiled variants
+ *   BRG_CONV_STEM_CLASSES (flag), BRG_CONV_STEM_GX = n
+ *                             bf16 7x7 layer on a channel block of 4: per-class backward launches, grid size
+ *   BRG_CONV_WGT_PS = 1|2, BRG_CONV_WGT_TARGET = n
+ *                             weight gradient: slabs per step, number of workgroups aimed at */
+void brg_tuning_reload(void);
+
 /* ---------------------------------------------------------------------------
  * Batch-reduce GEMM (paper section 2, the defining equation and Algorithm 1):
  *

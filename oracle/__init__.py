@@ -427,7 +427,8 @@ def lstm_bwd(d: LstmShape, x, W4, R4, h0, s0, h, s, gates, dh, ds_last=None):
 
 
 def rel_fro(got, want) -> float:
-    """Relative Frobenius error ||got - want||_F / ||want||_F in float64 (0/0 -> 0)."""
+    """Relative Frobenius error ||got - want||_F / ||want||_F in float64 (0/0 -> 0).
+    Pinned by hand values in tests/test_oracle_metrics.py."""
     g = np.asarray(got, dtype=np.float64).ravel()
     w = np.asarray(want, dtype=np.float64).ravel()
     den = np.linalg.norm(w)
@@ -435,3 +436,41 @@ def rel_fro(got, want) -> float:
     if den == 0.0:
         return 0.0 if num == 0.0 else float("inf")
     return float(num / den)
+
+
+def bf16_ulp(x) -> np.ndarray:
+    """Spacing of bf16 numbers (8 significant bits) at magnitude |x|: 2**(floor(log2|x|) - 7); 0 at x == 0."""
+    a = np.abs(np.asarray(x, dtype=np.float64))
+    _, e = np.frexp(a)                       # a = m * 2**e, 0.5 <= m < 1  =>  floor(log2 a) = e - 1
+    return np.where(a > 0, np.ldexp(1.0, e - 8), 0.0)
+
+
+def elem_bound(got, want, out_bf16=False, widen=1.0) -> np.ndarray:
+    """Per-element error bound that goes beside the Frobenius norm in the parity tests.
+
+    fp32 result of an fp32-accumulated sum:   1e-5 * widen * (|want| + rms(want))
+    bf16 result (one RNE rounding of such a sum): the same plus one bf16 spacing at max(|got|, |want|)
+    (the two sides round sums that differ by the fp32 term, so they land on the same or on neighbouring
+    bf16 numbers).  ``widen`` > 1 is for reductions much longer than 4096 terms and for results that pass
+    through several dependent steps; every use states its reason."""
+    w = np.abs(np.asarray(want, dtype=np.float64))
+    rms = float(np.sqrt(np.mean(w * w))) if w.size else 0.0
+    b = 1e-5 * widen * (w + rms)
+    if out_bf16:
+        b = b + bf16_ulp(np.maximum(w, np.abs(np.asarray(got, dtype=np.float64))))
+    return b
+
+
+def elem_excess(got, want, out_bf16=False, widen=1.0):
+    """(max over elements of |got - want| / elem_bound, flat index of that element); <= 1 passes.
+    A non-finite ``got`` gives inf.  0/0 counts as 0."""
+    g = np.asarray(got, dtype=np.float64).ravel()
+    w = np.asarray(want, dtype=np.float64).ravel()
+    if g.size == 0:
+        return 0.0, -1
+    b = elem_bound(g, w, out_bf16, widen)
+    err = np.abs(g - w)
+    ratio = np.where(err == 0, 0.0, err / np.where(b > 0, b, np.finfo(np.float64).tiny))
+    ratio = np.where(np.isfinite(g), ratio, np.inf)
+    j = int(np.argmax(ratio))
+    return float(ratio[j]), j

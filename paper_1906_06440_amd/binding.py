@@ -18,7 +18,7 @@ __all__ = [
     "ConvDesc", "FcDesc", "LstmDesc",
     "brg_gemm", "brg_gemm_strided", "brg_conv_ws_bytes", "brg_conv_fwd", "brg_conv_bwd_data", "brg_conv_bwd_wgt",
     "brg_conv_bwd_wgt_ws_bytes", "brg_fc_fwd", "brg_fc_bwd", "brg_fc_bwd_chain", "brg_lstm_fwd", "brg_lstm_bwd",
-    "brg_lstm_bwd_ws_bytes", "EXPORTS",
+    "brg_lstm_bwd_ws_bytes", "brg_tuning_reload", "EXPORTS",
 ]
 
 F32, BF16 = 0, 1
@@ -29,7 +29,7 @@ _STATUS = {0: "BRG_OK", 1: "BRG_EINVAL", 2: "BRG_EALIGN", 3: "BRG_EUNSUPPORTED",
 EXPORTS = [
     "brg_last_error", "brg_version", "brg_gemm", "brg_gemm_strided", "brg_conv_ws_bytes", "brg_conv_fwd",
     "brg_conv_bwd_data", "brg_conv_bwd_wgt", "brg_conv_bwd_wgt_ws_bytes", "brg_fc_fwd", "brg_fc_bwd", "brg_fc_bwd_chain",
-    "brg_lstm_fwd", "brg_lstm_bwd", "brg_lstm_bwd_ws_bytes",
+    "brg_lstm_fwd", "brg_lstm_bwd", "brg_lstm_bwd_ws_bytes", "brg_tuning_reload",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -81,6 +81,8 @@ def load():
     lib.brg_conv_bwd_data.argtypes = [C.POINTER(ConvDesc), ci, ci, vp, vp, vp, vp, vp]
     lib.brg_conv_bwd_wgt.argtypes = [C.POINTER(ConvDesc), ci, vp, vp, vp, vp, vp]
     lib.brg_conv_bwd_wgt_ws_bytes.argtypes = [C.POINTER(ConvDesc), ci]
+    lib.brg_tuning_reload.argtypes = []
+    lib.brg_tuning_reload.restype = None
     lib.brg_fc_fwd.argtypes = [C.POINTER(FcDesc), ci, ci, vp, vp, vp, ci, vp, vp]
     lib.brg_fc_bwd.argtypes = [C.POINTER(FcDesc), ci, vp, vp, vp, vp, ci, vp, vp, vp, vp, vp]
     lib.brg_fc_bwd_chain.argtypes = [C.POINTER(FcDesc), ci, vp, vp, vp, vp, ci, ci, vp, vp, vp, vp, vp]
@@ -89,7 +91,7 @@ def load():
     lib.brg_lstm_bwd_ws_bytes.argtypes = [C.POINTER(LstmDesc)]
     for name in EXPORTS:
         if name not in ("brg_last_error", "brg_version", "brg_conv_ws_bytes", "brg_conv_bwd_wgt_ws_bytes",
-                        "brg_lstm_bwd_ws_bytes"):
+                        "brg_lstm_bwd_ws_bytes", "brg_tuning_reload"):
             getattr(lib, name).restype = ci
     lib.brg_conv_ws_bytes.restype = i64
     lib.brg_conv_bwd_wgt_ws_bytes.restype = i64
@@ -166,6 +168,11 @@ def brg_conv_bwd_wgt_ws_bytes(desc: ConvDesc, dtype) -> int:
 def brg_conv_bwd_wgt(desc: ConvDesc, dtype, I, dO, dWt, ws=None, stream=None):
     _check(load().brg_conv_bwd_wgt(C.byref(desc), dtype, _ptr(I), _ptr(dO), _ptr(dWt), _ptr(ws),
                                    _stream(stream)))
+
+
+def brg_tuning_reload():
+    """Read the tuning-override environment variables again (they are read once, at the first call)."""
+    load().brg_tuning_reload()
 
 
 def brg_fc_fwd(desc: FcDesc, dtype, out_dtype, X, Wt, bias, act, Y, stream=None):

@@ -15,7 +15,7 @@
 // statement so that no use can be scheduled ahead of it.
 #pragma once
 
-#include "brg_block_tile.hpp"
+#include "brg_block_args.hpp"
 
 namespace brg {
 

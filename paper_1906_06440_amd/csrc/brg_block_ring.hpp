@@ -222,7 +222,7 @@ template <bool AKF, bool BKF> __global__ __launch_bounds__(512) void block_ring_
 // chains shorter than the ring go to the double-buffered kernel
 template <bool A_KFAST, bool B_KFAST> static int launch_block_ring(BlockTileArgs &a, hipStream_t s, const char *who)
 {
-    if (a.chain < 4 || getenv("BRG_NO_RING")) return launch_block_dma<A_KFAST, B_KFAST>(a, s, who);
+    if (a.chain < 4 || knobs().no_ring.set) return launch_block_dma<A_KFAST, B_KFAST>(a, s, who);
     a.xcd_patch = (a.tiles_m == 16 && a.tiles_n == 16) ? 1 : 0;
     auto kern = block_ring_f32<A_KFAST, B_KFAST>;
     static thread_local int allowed_on = -1;

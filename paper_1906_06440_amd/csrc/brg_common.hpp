@@ -9,6 +9,7 @@
 #include <type_traits>
 
 #include "brg.h"
+#include "brg_knobs.hpp"
 
 namespace brg {
 

@@ -449,7 +449,7 @@ static Bf16Plan plan_view_bf16(const ConvView &v, int grids = 1)
     // layers; wider rows cross less often and gain nothing, 7x7 tiles lose more to the larger halo than
     // they gain).
     if (v.str == 1 && v.R * v.S > 1 && a.Cb > 1 && a.Q >= 8 && a.Q < 16 &&
-        !(getenv("BRG_CONV_PITCH") && atoi(getenv("BRG_CONV_PITCH")) == 0))
+        !(knobs().conv_pitch.set && knobs().conv_pitch.val == 0))
         a.Wp += ((a.Q - a.Wp) % 8 + 8) % 8;
     a.trg = (CT_NG * 16) / a.Q;
     a.total_rows = a.N * a.P;
@@ -497,7 +497,7 @@ static Bf16Plan plan_view_bf16(const ConvView &v, int grids = 1)
     // device and a kernel variant that fits the register file (the strided 3x3 variant does not).
     pl.KW = a.Kb >= 8 ? 2 : 1;
     if (pl.KW == 2 && (grids * a.ntiles * ((a.Kb + 7) / 8) < 192 || pl.key == 33228)) pl.KW = 1;
-    if (const char *e = getenv("BRG_CONV_KW")) pl.KW = atoi(e) == 1 ? 1 : (atoi(e) == 2 && a.Kb >= 8 && pl.key != 33228 ? 2 : pl.KW);   // tuning knob
+    if (knobs().conv_kw.set) pl.KW = knobs().conv_kw.val == 1 ? 1 : (knobs().conv_kw.val == 2 && a.Kb >= 8 && pl.key != 33228 ? 2 : pl.KW);   // tuning knob
     int plane = nv_max * a.Wp * 16;
     plane = ((plane + 255) / 256) * 256 + 64;
     a.plane_bytes = plane;
@@ -578,7 +578,7 @@ static bool conv1x1_bf16_covers(const ConvView &v)
     if (npix >= (1 << 22) || (int64_t)v.N * v.Cb * v.Hin * v.Win * 16 >= (1ll << 31) ||
         (int64_t)v.N * v.Kb * v.Hout * v.Wout * 16 >= (1ll << 31))
         return false;
-    return !getenv("BRG_CONV_NO1X1");
+    return !knobs().conv_no1x1.set;
 }
 
 // `wtr`: Wt is in the stored layout of the forward pass (feature index contiguous inside a block) and the
@@ -604,8 +604,8 @@ static int conv1x1_bf16_launch(const ConvView &v, const void *I, const void *Wt,
     auto waves = [&](int kw, int pg) { return ((npix + 16 * pg - 1) / (16 * pg)) * ((v.Kb + kw - 1) / kw); };
     if (waves(KW, PG) < 2048) PG = 2;
     while (KW > 1 && waves(KW, PG) < 2048) KW >>= 1;
-    if (const char *e = getenv("BRG_CONV_1X1_KW")) { int x = atoi(e); if (x == 1 || x == 2 || x == 4) KW = x; }   // tuning knobs
-    if (const char *e = getenv("BRG_CONV_1X1_PG")) { int x = atoi(e); if (x == 2 || x == 4) PG = x; }
+    if (knobs().conv_1x1_kw.set) { int x = knobs().conv_1x1_kw.val; if (x == 1 || x == 2 || x == 4) KW = x; }   // tuning knobs
+    if (knobs().conv_1x1_pg.set) { int x = knobs().conv_1x1_pg.val; if (x == 2 || x == 4) PG = x; }
     // long reduction on few pixels: the workgroup-tiled kernel (operands shared through LDS), when all its
     // workgroups are resident at once (two per CU); with at most half as many 128 x 128 tiles as CUs, 128 x 64 tiles
     {
@@ -616,9 +616,9 @@ static int conv1x1_bf16_launch(const ConvView &v, const void *I, const void *Wt,
         // tiles than that: the streaming kernel's scattered lines cost it more than the tiled one
         const bool strided = (v.sub == 2 || v.osub == 2) && v.Cb >= 16 && units % 4 == 0;
         tiled = tiled || strided;
-        if (const char *e = getenv("BRG_CONV_1X1_LDS")) tiled = atoi(e) != 0 && units % 4 == 0;   // tuning knobs
+        if (knobs().conv_1x1_lds.set) tiled = knobs().conv_1x1_lds.val != 0 && units % 4 == 0;   // tuning knobs
         int ngw = (t128 <= 128 || (v.osub == 2 && t128 > 512)) ? 2 : 4;
-        if (const char *e = getenv("BRG_CONV_1X1_LDS_NGW")) { int x = atoi(e); if (x == 2 || x == 4) ngw = x; }
+        if (knobs().conv_1x1_lds_ngw.set) { int x = knobs().conv_1x1_lds_ngw.val; if (x == 2 || x == 4) ngw = x; }
         if (tiled) {
             a.tiles_x = (int)((npix + 32 * ngw - 1) / (32 * ngw));
             a.tiles_y = (v.Kb + 7) / 8;
@@ -628,7 +628,7 @@ static int conv1x1_bf16_launch(const ConvView &v, const void *I, const void *Wt,
             // stream the smaller operand through each XCD's L2 (activation bytes count with the lines that a
             // sub-sampled read wastes)
             a.pixel_major = npix * v.Cb * 32 * v.sub > (int64_t)v.Kb * v.Cb * 512;
-            if (const char *e = getenv("BRG_CONV_1X1_LDS_PM")) a.pixel_major = atoi(e) != 0;   // tuning knob
+            if (knobs().conv_1x1_lds_pm.set) a.pixel_major = knobs().conv_1x1_lds_pm.val != 0;   // tuning knob
             dim3 g3((unsigned)a.tiles);
             if (ngw == 4) {
                 if (wtr) hipLaunchKernelGGL((conv1x1_bf16_lds<true, 4, 4>), g3, dim3(256), 0, s, a);
@@ -642,7 +642,7 @@ static int conv1x1_bf16_launch(const ConvView &v, const void *I, const void *Wt,
     }
     // deep reduction on few pixels: split the channel blocks between the waves of a workgroup
     bool split = v.Cb >= 64 && v.Kb <= 32 && npix <= 16384;
-    if (const char *e = getenv("BRG_CONV_1X1_SPLIT")) split = atoi(e) != 0 && v.Cb >= 8;   // tuning knob
+    if (knobs().conv_1x1_split.set) split = knobs().conv_1x1_split.val != 0 && v.Cb >= 8;   // tuning knob
     if ((wtr && !ws) || zsib) split = false;
     if (split) {
         if (wtr) {
@@ -661,7 +661,7 @@ static int conv1x1_bf16_launch(const ConvView &v, const void *I, const void *Wt,
         return check_launch("brg_conv (1x1 bf16, split reduction) launch");
     }
     int wf = 4;
-    if (const char *e = getenv("BRG_CONV_1X1_WF")) { int x = atoi(e); if (x == 1 || x == 2 || x == 4) wf = x; }
+    if (knobs().conv_1x1_wf.set) { int x = knobs().conv_1x1_wf.val; if (x == 1 || x == 2 || x == 4) wf = x; }
     a.wf_log2 = wf == 4 ? 2 : (wf == 2 ? 1 : 0);
     const int64_t nchunk = (npix + 16 * PG - 1) / (16 * PG);
     dim3 grid((unsigned)((nchunk + 4 / wf - 1) / (4 / wf)), (unsigned)((v.Kb + wf * KW - 1) / (wf * KW)));
@@ -725,14 +725,14 @@ template <int TR, int TS> static int conv_stem_bwd_go(const StemBwdArgs &a, hipS
 static int conv_stem_bwd_launch(const ConvDims &d, const void *dO, const void *Wt, void *dI, hipStream_t s)
 {
     // 64 features on an even-sized image: all four parity classes in one pass over dO
-    if (d.Kb == 4 && d.H == 2 * d.P && d.W == 2 * d.Q && !getenv("BRG_CONV_STEM_CLASSES")) {
+    if (d.Kb == 4 && d.H == 2 * d.P && d.W == 2 * d.Q && !knobs().conv_stem_classes.set) {
         StemBwdFusedArgs a = {};
         a.dO = dO; a.Wt = Wt; a.dI = dI;
         a.N = d.N; a.H = d.H; a.W = d.W; a.P = d.P; a.Q = d.Q;
         a.tiles_r = (d.P + SF_T - 1) / SF_T; a.tiles_c = (d.Q + SF_T - 1) / SF_T;
         a.ntiles = d.N * a.tiles_r * a.tiles_c;
         int gx = a.ntiles < 512 ? a.ntiles : 512;
-        if (const char *e = getenv("BRG_CONV_STEM_GX")) { int x = atoi(e); if (x > 0 && x <= a.ntiles) gx = x; }   // tuning knob
+        if (knobs().conv_stem_gx.set) { int x = knobs().conv_stem_gx.val; if (x > 0 && x <= a.ntiles) gx = x; }   // tuning knob
         hipLaunchKernelGGL(conv_stem_bwd_fused_bf16, dim3(gx), dim3(256), 0, s, a);
         return check_launch("brg_conv_bwd_data (stem, fused classes) launch");
     }
@@ -865,7 +865,7 @@ extern "C" int brg_conv_fwd(const brg_conv_desc_t *desc, brg_dtype_t dtype, brg_
     }
     if (dtype == BRG_F32 && out_dtype == BRG_F32) {
         ConvTilePlan pl = plan_conv_tile(d, false);
-        if (pl.ok && !getenv("BRG_CONV_GENERAL")) {
+        if (pl.ok && !knobs().conv_general.set) {
             if (ws) {
                 // weights: every 16x16 block transposed into the workspace: one float4 per matrix-core operand
                 BRG_REQUIRE(aligned16(ws), BRG_EALIGN, "brg_conv_fwd: workspace not 16-byte aligned");
@@ -887,8 +887,8 @@ extern "C" int brg_conv_fwd(const brg_conv_desc_t *desc, brg_dtype_t dtype, brg_
         const bool have_view = conv_fwd_view(d, &v);
         const bool is1x1 = have_view && conv1x1_bf16_covers(v);
         if (have_view && !is1x1) pl = plan_view_bf16(v);
-        if (is1x1 && !getenv("BRG_CONV_GENERAL")) return conv1x1_bf16_launch(v, I, Wt, O, bias, act, true, ws, s);
-        if (pl.ok && bf16_key_known(pl.key) && ws && !getenv("BRG_CONV_GENERAL")) {
+        if (is1x1 && !knobs().conv_general.set) return conv1x1_bf16_launch(v, I, Wt, O, bias, act, true, ws, s);
+        if (pl.ok && bf16_key_known(pl.key) && ws && !knobs().conv_general.set) {
             // weights: every 16x16 block transposed into the workspace, so that the reduction index is
             // contiguous for the matrix-core operand loads
             BRG_REQUIRE(aligned16(ws), BRG_EALIGN, "brg_conv_fwd: workspace not 16-byte aligned");
@@ -924,14 +924,14 @@ extern "C" int brg_conv_bwd_data(const brg_conv_desc_t *desc, brg_dtype_t dtype,
     }
     if (dtype == BRG_F32 && out_dtype == BRG_F32) {
         ConvTilePlan pl = plan_conv_tile(d, true);
-        if (pl.ok && !getenv("BRG_CONV_GENERAL"))
+        if (pl.ok && !knobs().conv_general.set)
             return conv_tile_f32_launch<1>(pl, dO, Wt, dI, nullptr, BRG_ACT_NONE, s);
         return conv_bwd_data_launch<float, float>(d, dO, Wt, dI, s);
     }
     if (dtype == BRG_BF16 && out_dtype == BRG_F32) return conv_bwd_data_launch<bf16_t, float>(d, dO, Wt, dI, s);
     if (dtype == BRG_BF16 && out_dtype == BRG_BF16) {
         // one tiled pass per stride x stride parity class of the input pixels
-        if (d.sh == d.sw && d.sh <= 2 && !getenv("BRG_CONV_GENERAL")) {
+        if (d.sh == d.sw && d.sh <= 2 && !knobs().conv_general.set) {
             Bf16Plan plans[4];
             ConvView views[4];
             int np = 0, nclass = d.sh * d.sw;
@@ -958,7 +958,7 @@ extern "C" int brg_conv_bwd_data(const brg_conv_desc_t *desc, brg_dtype_t dtype,
             if (all_ok && np > 0) {
                 // 1x1 with stride 2: only class (0, 0) has a tap; its kernel writes the zero pixels itself
                 const bool zsib = holes && np == 1 && d.sh == 2 && conv1x1_bf16_covers(views[0]) && views[0].osub == 2 &&
-                                  views[0].ooh == 0 && views[0].oow == 0 && !getenv("BRG_CONV_ZEROFILL");
+                                  views[0].ooh == 0 && views[0].oow == 0 && !knobs().conv_zerofill.set;
                 if (zsib) return conv1x1_bf16_launch(views[0], dO, Wt, dI, nullptr, BRG_ACT_NONE, false, nullptr, s, true);
                 if (holes) {
                     const int64_t n16 = (int64_t)d.N * d.C * d.H * d.W * 2 / 16;
@@ -974,7 +974,7 @@ extern "C" int brg_conv_bwd_data(const brg_conv_desc_t *desc, brg_dtype_t dtype,
                         if (plans[i].key == 21142) fused[1] = i;
                         if (plans[i].key == 22142) fused[2] = i;
                     }
-                bool fuse = fused[0] >= 0 && fused[1] >= 0 && fused[2] >= 0 && !getenv("BRG_CONV_NOFUSE");
+                bool fuse = fused[0] >= 0 && fused[1] >= 0 && fused[2] >= 0 && !knobs().conv_nofuse.set;
                 for (int j = 1; j < 3 && fuse; ++j) {
                     const Bf16Plan &p0 = plans[fused[0]], &pj = plans[fused[j]];
                     fuse = p0.KW == pj.KW && p0.grid.x == pj.grid.x && p0.grid.y == pj.grid.y;

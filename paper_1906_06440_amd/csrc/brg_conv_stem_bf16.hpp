@@ -172,7 +172,7 @@ template <int KB, bool PACKED> __global__ __launch_bounds__(256, 2) void conv_st
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Backward by data of the same layer (the "dual convolution" of paper section 3.2.3): dI has one channel
+// Backward by data of the same layer (the "dual convolution" of the close of paper section 3.2.2): dI has one channel
 // block of 4.  The input pixels (h, w) = (2i + a, 2j + b) of parity class (a, b) receive the filter taps
 // r = r0 + 2tr, s = s0 + 2ts (r0 = (a + 1) % 2, 3 or 4 taps per direction) from dO pixel
 // (i + drmax - tr, j + dsmax - ts): per class a stride-1 pass over dO, one launch each.

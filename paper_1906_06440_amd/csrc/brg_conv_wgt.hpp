@@ -824,7 +824,7 @@ static ConvWgtPlan conv_wgt_plan(int64_t N, int64_t C, int64_t H, int64_t W, int
     if (R == 7 && S == 7 && sh == 2 && sw == 2 && ph == 3 && pw == 3 && bc == 4 && C == 4 && bk == 16) {
         // the stem on one channel block of 4: even widths up to 224, output rows of at least 32 pixels
         const int64_t P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1, Kb = K / 16;
-        if (W % 2 || W > 224 || Q < 32 || Kb % 4 || N * H * W >= (1ll << 30) || getenv("BRG_CONV_WGT_GENERAL")) return p;
+        if (W % 2 || W > 224 || Q < 32 || Kb % 4 || N * H * W >= (1ll << 30) || knobs().conv_wgt_general.set) return p;
         p.taps = 49; p.stem = true; p.WT = 2;
         p.steps_per_img = (int)((P * Q + 31) / 32);
         p.steps_total = (int)(N * p.steps_per_img);
@@ -841,7 +841,7 @@ static ConvWgtPlan conv_wgt_plan(int64_t N, int64_t C, int64_t H, int64_t W, int
     const int64_t P = (H - 1) / sh + 1, Q = (W - 1) / sw + 1;     // output size of the layers handled here
     const int64_t Cb = C / 16, Kb = K / 16, HW = P * Q;
     if (N * H * W >= (1ll << 30)) return p;
-    if (Cb % 4 || Kb % 4 || HW < 32 || N * HW >= (1ll << 30) || getenv("BRG_CONV_WGT_GENERAL")) return p;
+    if (Cb % 4 || Kb % 4 || HW < 32 || N * HW >= (1ll << 30) || knobs().conv_wgt_general.set) return p;
     p.taps = is1 ? 1 : 9;
     p.s2 = is3s2;
     p.WT = (!f32 && is1 && Cb % 8 == 0 && Kb % 8 == 0 && (Cb / 8) * (Kb / 8) >= 16) ? 4 : 2;
@@ -849,7 +849,7 @@ static ConvWgtPlan conv_wgt_plan(int64_t N, int64_t C, int64_t H, int64_t W, int
     p.ps = 1;
     if (is1 && !f32) {
         p.ps = 2;
-        if (const char *e = getenv("BRG_CONV_WGT_PS")) { const int x = atoi(e); if (x == 1 || x == 2) p.ps = x; }   // tuning knob
+        if (knobs().conv_wgt_ps.set) { const int x = knobs().conv_wgt_ps.val; if (x == 1 || x == 2) p.ps = x; }   // tuning knob
     }
     p.steps_per_img = (int)((HW + 32 * p.ps - 1) / (32 * p.ps));
     p.steps_total = (int)(N * p.steps_per_img);
@@ -857,7 +857,7 @@ static ConvWgtPlan conv_wgt_plan(int64_t N, int64_t C, int64_t H, int64_t W, int
     // staging loads every step); 1024 where the partial sums then still stay within 16 MB
     int64_t target = 512;
     if (is1 && nb >= 8 && Cb * Kb * 1024 * (1024 / nb) <= (16ll << 20)) target = 1024;
-    if (const char *e = getenv("BRG_CONV_WGT_TARGET")) { const int x = atoi(e); if (x > 0) target = x; }   // tuning knob
+    if (knobs().conv_wgt_target.set) { const int x = knobs().conv_wgt_target.val; if (x > 0) target = x; }   // tuning knob
     int64_t ns = (target + nb - 1) / nb;
     if (ns > (int64_t)p.steps_total * p.ps / 8) ns = (int64_t)p.steps_total * p.ps / 8;   // at least 256 pixels per range
     if (ns < 1) ns = 1;

@@ -234,7 +234,7 @@ static int fc_dims(const brg_fc_desc_t *desc, FcDims *d, const char *who)
 // 1x1 convolution kernels (forward with bias and activation, backward by data).
 static bool fc_is_conv1x1(const FcDims &d)
 {
-    return d.bc == 16 && d.bk == 16 && !getenv("BRG_FC_GENERAL");
+    return d.bc == 16 && d.bk == 16 && !knobs().fc_general.set;
 }
 
 static brg_conv_desc_t fc_as_conv1x1(const FcDims &d)
@@ -245,7 +245,7 @@ static brg_conv_desc_t fc_as_conv1x1(const FcDims &d)
 
 static bool fc_blocks_64(const FcDims &d)
 {
-    return d.bn == 64 && d.bc == 64 && d.bk == 64 && !getenv("BRG_FC_GENERAL");
+    return d.bn == 64 && d.bc == 64 && d.bk == 64 && !knobs().fc_general.set;
 }
 
 template <typename TIn, typename TOut>
@@ -321,7 +321,7 @@ extern "C" int brg_fc_fwd(const brg_fc_desc_t *desc, brg_dtype_t dtype, brg_dtyp
         j.a_tile = (int64_t)d.Cb * 4096; j.a_chain = 4096; j.b_tile = (int64_t)d.Cb * 4096; j.b_chain = 4096;
         j.c_tile_m = 4096; j.c_tile_n = (int64_t)d.Kb * 4096; j.a_ld = j.b_ld = j.c_ld = 64;
         j.a_kfast = 0; j.b_kfast = 1;
-        if (!getenv("BRG_FC_G64")) {
+        if (!knobs().fc_g64.set) {
             // a lone GEMM: one 8-wave workgroup per block of Y, the chain split between two wave groups
             BlockTileArgs b = {};
             b.A = j.A; b.B = j.B; b.C = j.C; b.bias = bias; b.act = act;
@@ -330,7 +330,7 @@ extern "C" int brg_fc_fwd(const brg_fc_desc_t *desc, brg_dtype_t dtype, brg_dtyp
             b.c_tile_m = j.c_tile_m; b.c_tile_n = j.c_tile_n; b.a_ld = b.b_ld = b.c_ld = 64;
             return launch_block_ring<false, true>(b, s, "brg_fc_fwd launch");
         }
-        return launch_g64(a, atoi(getenv("BRG_FC_G64")) == 32 ? 32 : 64, 0, s, "brg_fc_fwd launch");
+        return launch_g64(a, knobs().fc_g64.val == 32 ? 32 : 64, 0, s, "brg_fc_fwd launch");
     }
     if (dtype == BRG_BF16 && out_dtype == BRG_BF16 && fc_is_conv1x1(d)) {
         const brg_conv_desc_t c = fc_as_conv1x1(d);

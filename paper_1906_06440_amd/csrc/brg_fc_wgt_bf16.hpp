@@ -150,7 +150,7 @@ static int launch_fc_mask_bf16(void *dst, const void *src, const void *mask, int
 
 static bool fc_wgt_bf16_applies(int Cb, int Kb, int bn)
 {
-    return Cb % 4 == 0 && Kb % 4 == 0 && bn % 32 == 0 && !getenv("BRG_FC_WGT_GENERAL");
+    return Cb % 4 == 0 && Kb % 4 == 0 && bn % 32 == 0 && !knobs().fc_wgt_general.set;
 }
 
 static int launch_fc_wgt_bf16(const FcWgtBf16Args &a, hipStream_t s, const char *who)

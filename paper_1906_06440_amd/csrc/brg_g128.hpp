@@ -350,8 +350,8 @@ static __global__ __launch_bounds__(512) void g128_kernel(G64Args args)   // (on
 // (BRG_FC_G128=0 never, =1 whenever the jobs have the right form).
 static bool g128_applies(const G64Args &a)
 {
-    const char *knob = getenv("BRG_FC_G128");
-    if (knob && atoi(knob) == 0) return false;
+    const bool knob = knobs().fc_g128.set;
+    if (knob && knobs().fc_g128.val == 0) return false;
     int wg = 0;
     for (int j = 0; j < a.njobs; ++j) {
         const G64Job &J = a.job[j];

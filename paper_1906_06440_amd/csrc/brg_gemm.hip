@@ -5,7 +5,6 @@
 
 #include "brg_block_dma.hpp"
 #include "brg_block_ring.hpp"
-#include "brg_block_tile.hpp"
 #include "brg_engine.hpp"
 
 namespace brg {
@@ -131,14 +130,13 @@ static int gemm_common(int dtype, int out_dtype, int64_t m, int64_t n, int64_t k
     // 64 x 64 x 64 fp32 blocks at fixed strides: the dedicated block kernel
     if (!ptrs && dtype == BRG_F32 && out_dtype == BRG_F32 && count > 0 && k == 64 && m % 64 == 0 && n % 64 == 0 &&
         lda % 4 == 0 && ldb % 4 == 0 && ldc % 4 == 0 && strideA % 4 == 0 && strideB % 4 == 0 &&
-        lda < (1 << 24) && ldb < (1 << 24) && ldc < (1 << 24) && !getenv("BRG_GEMM_GENERAL")) {
+        lda < (1 << 24) && ldb < (1 << 24) && ldc < (1 << 24) && !knobs().gemm_general.set) {
         BlockTileArgs a = {};
         a.A = (const float *)A; a.B = (const float *)B; a.C = (float *)C; a.bias = bias; a.act = act;
         a.tiles_m = (int)(m / 64); a.tiles_n = (int)(n / 64); a.chain = (int)count; a.alpha = alpha; a.beta = beta;
         a.a_tile = 64; a.a_chain = strideA; a.b_tile = 64 * ldb; a.b_chain = strideB;
         a.c_tile_m = 64; a.c_tile_n = 64 * ldc; a.a_ld = (int)lda; a.b_ld = (int)ldb; a.c_ld = (int)ldc;
-        if (!getenv("BRG_NO_DMA")) return launch_block_ring<false, true>(a, s, "brg_gemm_strided launch");
-        return launch_block_tile<false, true>(a, s, "brg_gemm_strided launch");
+        return launch_block_ring<false, true>(a, s, "brg_gemm_strided launch");
     }
 #define BRG_GEMM_GO(TI, TO)                                                                         \
     return ptrs ? launch_gemm<TI, TO, true>(m, n, k, lda, ldb, ldc, A_ptrs, B_ptrs, A, strideA, B,  \

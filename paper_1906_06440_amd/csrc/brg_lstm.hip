@@ -142,9 +142,42 @@ extern "C" int brg_lstm_fwd(const brg_lstm_desc_t *desc, brg_dtype_t dtype, cons
     // leave partial pre-activations in `gates`, then ONE persistent kernel for the recurrence.
     // Needs: 64-blocking, T*N a multiple of 64, N <= 64, K/4 <= number of CUs, a gates buffer and a
     // 16-byte workspace for the grid barrier (word 0: arrival counter, word 1: give-up flag).
-    if (d.bc == 64 && d.bk == 64 && ((int64_t)d.T * d.N) % 64 == 0 && d.N <= 64 && gates && ws &&
-        d.K / 4 <= 256 && (int64_t)d.T * NK < (1ll << 30) && !getenv("BRG_LSTM_GENERAL")) {
-        BRG_REQUIRE(aligned16(ws), BRG_EALIGN, "brg_lstm_fwd: workspace not 16-byte aligned");
+    bool fast = d.bc == 64 && d.bk == 64 && ((int64_t)d.T * d.N) % 64 == 0 && d.N <= 64 && gates && ws &&
+                d.K / 4 <= 256 && (int64_t)d.T * NK < (1ll << 30) && !knobs().lstm_general.set;
+    if (ws) BRG_REQUIRE(aligned16(ws), BRG_EALIGN, "brg_lstm_fwd: workspace not 16-byte aligned");
+    if (fast) {
+        // All K/4 workgroups of the resident kernel must be on the device together (they wait for each other
+        // every time step).  A workgroup takes more than half of a compute unit's LDS, so that means one per
+        // compute unit; the occupancy query confirms it for this device (asked once per thread and device).
+        // Where they do not fit, the layer runs as one launch per time step instead.
+        static thread_local int cap_dev = -1, cap = 0;
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess && dev != cap_dev) {
+            int per_cu = 0, ncu = 0;
+            e = hipFuncSetAttribute((const void *)lstm_rec_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LR_SMEM);
+            if (e == hipSuccess)
+                e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)lstm_rec_kernel, 512, LR_SMEM);
+            if (e == hipSuccess) e = hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev);
+            if (e == hipSuccess) {
+                cap = per_cu * ncu;
+                cap_dev = dev;
+            }
+        }
+        if (e != hipSuccess) return fail(BRG_EHIP, "brg_lstm_fwd: set-up: %s", hipGetErrorString(e));
+        if (cap < d.K / 4) fast = false;
+    }
+    if (ws) {   // both words start at zero on either path, so the caller can always read word 1 afterwards
+        hipLaunchKernelGGL(lstm_sync_reset, dim3(1), dim3(64), 0, st, (unsigned *)ws);
+        int rc = check_launch("brg_lstm_fwd (barrier reset) launch");
+        if (rc) return rc;
+    }
+
+    // ---- fast path: input projections of all time steps as four batch-reduce GEMMs (bias fused) that
+    // leave partial pre-activations in `gates`, then ONE resident kernel for the recurrence.
+    // Needs: 64-blocking, T*N a multiple of 64, N <= 64, K/4 workgroups resident together, a gates buffer and a
+    // 16-byte workspace for the grid barrier (word 0: arrival counter, word 1: give-up flag).
+    if (fast) {
         const int64_t TNK = (int64_t)d.T * NK;
         G64Args a = {};
         a.njobs = 4;
@@ -161,31 +194,19 @@ extern "C" int brg_lstm_fwd(const brg_lstm_desc_t *desc, brg_dtype_t dtype, cons
         }
         int rc = launch_g64(a, 64, 0, st, "brg_lstm_fwd (input projection) launch");
         if (rc) return rc;
-        hipLaunchKernelGGL(lstm_sync_reset, dim3(1), dim3(64), 0, st, (unsigned *)ws);
-        rc = check_launch("brg_lstm_fwd (barrier reset) launch");
-        if (rc) return rc;
         LstmRecArgs r;
         r.R4 = (const float *)R4; r.h0 = (const float *)h0; r.s0 = (const float *)s0;
         r.h = (float *)h; r.s = (float *)s; r.gates = (float *)gates; r.sync = (unsigned *)ws;
         r.T = d.T; r.N = d.N; r.K = d.K; r.spin_limit = 200000u;
-        hipError_t e = hipFuncSetAttribute((const void *)lstm_rec_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)LR_SMEM);
-        if (e != hipSuccess) return fail(BRG_EHIP, "brg_lstm_fwd: set-up: %s", hipGetErrorString(e));
-        // All K/4 workgroups must be resident together (they wait for each other every time step).  A
-        // workgroup takes more than half of a compute unit's LDS, so that means one per compute unit;
-        // the occupancy query confirms it for this device.  Should other work keep compute units busy
-        // for longer than the spin limit, the kernel gives up and reports through sync[1].
-        int per_cu = 0, dev = 0, ncu = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)lstm_rec_kernel, 512, LR_SMEM);
-        if (e == hipSuccess) e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess) return fail(BRG_EHIP, "brg_lstm_fwd: set-up: %s", hipGetErrorString(e));
-        BRG_REQUIRE((int64_t)per_cu * ncu >= d.K / 4, BRG_EUNSUPPORTED,
-                    "brg_lstm_fwd: %d workgroups cannot be resident together on %d compute units", d.K / 4, ncu);
+        // Should other work keep compute units busy for longer than the spin limit, the kernel gives up and
+        // reports through sync[1]; the kernel enqueued after it then overwrites h, s and gates with NaN, so
+        // that a run that gave up cannot pass for a result.
         hipLaunchKernelGGL(lstm_rec_kernel, dim3(d.K / 4), dim3(512), LR_SMEM, st, r);
         rc = check_launch("brg_lstm_fwd (recurrence) launch");
         if (rc) return rc;
-        return BRG_OK;
+        hipLaunchKernelGGL(lstm_rec_poison, dim3(256), dim3(256), 0, st, (const unsigned *)ws, (float *)h, (float *)s,
+                           (float *)gates, TNK);
+        return check_launch("brg_lstm_fwd (give-up check) launch");
     }
 
     for (int t = 0; t < d.T; ++t) {

@@ -230,7 +230,7 @@ extern "C" int brg_lstm_bwd(const brg_lstm_desc_t *desc, brg_dtype_t dtype, cons
     const int64_t TNK = (int64_t)d.T * NK;
     float *dz = (float *)ws, *dh_rec = dz + 4 * TNK, *dsb = dh_rec + 16 * (int64_t)NK;   // dh_rec: up to sixteen partial sums
     // 64-wide blocks and whole 64-row batch tiles: the GEMMs run on the 64 x 64 x 64 multi-job kernel
-    const bool fast = d.bc == 64 && d.bk == 64 && d.N % 64 == 0 && (int64_t)4 * d.K * d.K < (1ll << 31) && !getenv("BRG_LSTM_GENERAL");
+    const bool fast = d.bc == 64 && d.bk == 64 && d.N % 64 == 0 && (int64_t)4 * d.K * d.K < (1ll << 31) && !knobs().lstm_general.set;
     const float *hf = (const float *)h, *sf = (const float *)s, *gf = (const float *)gates, *dhf = (const float *)dh;
     const unsigned eg = (unsigned)((NK + 255) / 256);
 

@@ -25,3 +25,19 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+@pytest.fixture(autouse=True)
+def _tuning_overrides_follow_the_environment(monkeypatch):
+    """The library reads its tuning overrides from the environment once; tests that set one through
+    monkeypatch call `brg.brg_tuning_reload()` themselves, and this fixture reads the restored environment
+    again after every test so that no override leaks into the next one."""
+    yield
+    monkeypatch.undo()
+    try:
+        import paper_1906_06440_amd as brg
+        import os
+        if os.path.exists(brg.lib_path()):
+            brg.brg_tuning_reload()
+    except Exception:
+        pass

@@ -60,6 +60,8 @@ SHAPES = [  # m n k count lda ldb ldc
     (1, 1, 1, 1, 1, 1, 1), (5, 3, 7, 2, 5, 7, 5), (64, 64, 16, 3, 64, 16, 64), (70, 66, 19, 5, 72, 24, 80),
     (129, 33, 64, 2, 129, 64, 129), (200, 130, 40, 4, 208, 48, 200), (16, 300, 16, 36, 16, 32, 16),
     (64, 64, 64, 1, 64, 64, 64), (31, 257, 3, 9, 40, 4, 36),
+    # 64-deep blocks, m and n multiples of 64, chains of 4 and more: the ring kernel with alpha, beta, bias, activation
+    (128, 128, 64, 6, 128, 64, 128), (64, 192, 64, 4, 72, 68, 64), (64, 64, 64, 17, 64, 64, 64),
 ]
 
 
@@ -75,7 +77,7 @@ def test_shapes_ragged_tails(m, n, k, count, lda, ldb, ldc, dtype, out):
     for alpha, beta, b, act in [(1.0, 0.0, None, brg.ACT_NONE), (0.5, -1.5, bias, brg.ACT_RELU)]:
         got = _run_strided(A, B, m, n, k, lda, ldb, ldc, count, sa, sb, dtype, out, alpha, beta, C0, b, act)
         want = _oracle_strided(A, B, m, n, k, lda, ldb, ldc, count, sa, sb, dtype, out, alpha, beta, C0, b, act)
-        check(got[:, :m], want[:, :m], out if out == brg.BF16 else dtype, f"{m}x{n}x{k}x{count}")
+        check(got[:, :m], want[:, :m], dtype, f"{m}x{n}x{k}x{count}", out)
         # rows of C between m and ldc are never written
         ref_pad = as_seen_by_gpu(C0, out)[:, m:]
         assert np.array_equal(got[:, m:], ref_pad)
@@ -99,3 +101,14 @@ def test_sigmoid_tanh_epilogue_and_aliasing():
         got = _run_strided(A, A, 32, 32, 32, 32, 32, 32, 3, 1024, 1024, act=act)   # A aliases B
         want = _oracle_strided(A, A, 32, 32, 32, 32, 32, 32, 3, 1024, 1024, brg.F32, brg.F32, 1.0, 0.0, None, None, act)
         check(got, want, brg.F32, "act %d" % act)
+
+
+@pytest.mark.parametrize("knob", ["BRG_GEMM_GENERAL", "BRG_NO_RING"])
+def test_cfg1_on_the_other_kernels(monkeypatch, knob):
+    """The general tile kernel and the double-buffered block kernel on the cfg1 chain."""
+    monkeypatch.setenv(knob, "1")
+    brg.brg_tuning_reload()
+    A, B = wl.cfg1_brgemm()
+    want = np.zeros((64, 64), np.float32)
+    orc.brgemm(list(A), list(B), 64, 64, 64, 64, 64, 64, want)
+    check(_run_strided(A, B, 64, 64, 64, 64, 64, 64, 16, 4096, 4096), want, brg.F32, "cfg1 " + knob)

@@ -6,7 +6,7 @@ import torch
 import oracle as orc
 import paper_1906_06440_amd as brg
 import workloads as wl
-from gpu_util import as_seen_by_gpu, check, dev, empty, host
+from gpu_util import as_seen_by_gpu, check, dev, empty, host, workspace
 
 pytestmark = pytest.mark.gpu
 
@@ -50,8 +50,8 @@ def test_fc_fwd_bwd_small(N, C, K, bn, bc, bk, dtype):
         dX, dW, db = _bwd(d, dY, Y, X, W, act, dtype)
         rX, rW, rb = orc.fc_bwd(d, dYs, Y, Xs, Ws, act, dx_bf16=dtype == brg.BF16)
         check(dX, rX, dtype, "fc dX")
-        check(dW, rW, dtype, "fc dW")
-        check(db, rb, dtype, "fc db")
+        check(dW, rW, dtype, "fc dW", out=brg.F32)
+        check(db, rb, dtype, "fc db", out=brg.F32)
     assert (Y == 0).mean() > 0.2      # the ReLU case really masked something
 
 
@@ -60,7 +60,7 @@ def test_fc_optional_outputs_and_fp32_out_from_bf16():
     d = orc.FcShape(64, 64, 64)
     X, W = wl.uniform(rng, d.x_shape), wl.normal(rng, d.w_shape, 0.125)
     Y = _fwd(d, X, W, None, brg.ACT_NONE, brg.BF16, brg.F32)
-    check(Y, orc.fc_fwd(d, as_seen_by_gpu(X, brg.BF16), as_seen_by_gpu(W, brg.BF16)), brg.BF16, "bf16->fp32")
+    check(Y, orc.fc_fwd(d, as_seen_by_gpu(X, brg.BF16), as_seen_by_gpu(W, brg.BF16)), brg.BF16, "bf16->fp32", out=brg.F32)
     desc = brg.FcDesc(64, 64, 64, 64, 64, 64)
     dX = empty(d.x_shape, fill=7.0)
     brg.brg_fc_bwd(desc, brg.F32, dev(Y), None, dev(X), dev(W), brg.ACT_NONE, dX, None, None)
@@ -91,8 +91,8 @@ def test_fc_bwd_chain_fuses_producer_relu(N, C, K, bn, bc, bk, dtype):
     dX, dW, db = _bwd_chain(d, dY, None, X, W, brg.ACT_NONE, brg.ACT_RELU, dtype)
     rX, rW, rb = orc.fc_bwd(d, dYs, None, Xs, Ws, orc.ACT_NONE, dx_bf16=dtype == brg.BF16)
     check(dX, rX * (Xs > 0), dtype, "masked dX")
-    check(dW, rW, dtype, "dW")
-    check(db, rb, dtype, "db")
+    check(dW, rW, dtype, "dW", out=brg.F32)
+    check(db, rb, dtype, "db", out=brg.F32)
     assert (dX == 0).mean() > 0.3
 
 
@@ -105,6 +105,7 @@ def test_fc_bwd_128x64_tiles_forced(N, C, K, act_in, act, monkeypatch):
     fused producer mask on dX; the last shape has K/64 = 2, so its by-data chain is too short and the launch
     must fall back to the 64 x 64 kernel."""
     monkeypatch.setenv("BRG_FC_G128", "1")
+    brg.brg_tuning_reload()
     rng = np.random.default_rng(N + C + K)
     d = orc.FcShape(N, C, K, 64, 64, 64)
     X = np.maximum(wl.uniform(rng, d.x_shape), 0)
@@ -116,8 +117,8 @@ def test_fc_bwd_128x64_tiles_forced(N, C, K, act_in, act, monkeypatch):
     if act_in == brg.ACT_RELU:
         rX = rX * (X > 0)
     check(dX, rX, brg.F32, "dX")
-    check(dW, rW, brg.F32, "dW")
-    check(db, rb, brg.F32, "db")
+    check(dW, rW, brg.F32, "dW", out=brg.F32)
+    check(db, rb, brg.F32, "db", out=brg.F32)
 
 
 def test_config3_mlp_full_size():
@@ -135,8 +136,8 @@ def test_config3_mlp_full_size():
         dX, dW, db = _bwd(d, g, acts_gpu[l + 1], acts_gpu[l], Ws[l], brg.ACT_RELU)
         rX, rW, rb = orc.fc_bwd(d, g, acts_gpu[l + 1], acts_gpu[l], Ws[l], orc.ACT_RELU)
         check(dX, rX, brg.F32, "layer %d dX" % l)
-        check(dW, rW, brg.F32, "layer %d dW" % l)
-        check(db, rb, brg.F32, "layer %d db" % l)
+        check(dW, rW, brg.F32, "layer %d dW" % l, out=brg.F32)
+        check(db, rb, brg.F32, "layer %d db" % l, out=brg.F32)
         g = dX
     # the same chain the way the benchmark drives it: the ReLU backward of layer l-1 is fused into the
     # dX epilogue of layer l, so only the last layer masks its incoming gradient
@@ -150,13 +151,13 @@ def test_config3_mlp_full_size():
         if l > 0:
             rX = rX * (acts_gpu[l] > 0)
         check(dX, rX, brg.F32, "chain layer %d dZ" % l)
-        check(dW, rW, brg.F32, "chain layer %d dW" % l)
-        check(db, rb, brg.F32, "chain layer %d db" % l)
+        check(dW, rW, brg.F32, "chain layer %d dW" % l, out=brg.F32)
+        check(db, rb, brg.F32, "chain layer %d db" % l, out=brg.F32)
         g = dX
 
 
 def test_fc_paper_minibatch_1344():
-    """The minibatch the paper runs its MLP at (section 5.1: 1344 = 21 blocks of 64), C = K = 1024, fp32: forward
+    """The minibatch the paper runs its MLP at (section 4.1.3: 1344 = 21 blocks of 64), C = K = 1024, fp32: forward
     with bias + ReLU, then the fused backward launch with the ReLU mask and the producer mask."""
     X0, Ws, bs, dYl = wl.cfg3_mlp(N=1344, layers=1)
     d = orc.FcShape(1344, 1024, 1024)
@@ -166,8 +167,8 @@ def test_fc_paper_minibatch_1344():
     dX, dW, db = _bwd_chain(d, dYl, Y, X0, Ws[0], brg.ACT_RELU, brg.ACT_RELU)
     rX, rW, rb = orc.fc_bwd(d, dYl, Y, X0, Ws[0], orc.ACT_RELU)
     check(dX, rX * (X0 > 0), brg.F32, "dX")
-    check(dW, rW, brg.F32, "dW")
-    check(db, rb, brg.F32, "db")
+    check(dW, rW, brg.F32, "dW", out=brg.F32)
+    check(db, rb, brg.F32, "db", out=brg.F32)
 
 
 def test_fc_bf16_16_blocks_full_size_runs_as_1x1_convolution():
@@ -185,8 +186,8 @@ def test_fc_bf16_16_blocks_full_size_runs_as_1x1_convolution():
     dX, dW, db = _bwd(d, dY, None, X, W, brg.ACT_NONE, brg.BF16)
     rX, rW, rb = orc.fc_bwd(d, dYs, None, Xs, Ws, orc.ACT_NONE, dx_bf16=True)
     check(dX, rX, brg.BF16, "dX")
-    check(dW, rW, brg.BF16, "dW")
-    check(db, rb, brg.BF16, "db")
+    check(dW, rW, brg.BF16, "dW", out=brg.F32)
+    check(db, rb, brg.BF16, "db", out=brg.F32)
 
 
 @pytest.mark.parametrize("N,C,K,bn", [(256, 128, 192, 64), (128, 256, 128, 32), (1024, 1024, 1024, 64)])
@@ -202,12 +203,35 @@ def test_fc_bf16_16_blocks_masked_backward_with_workspace(N, C, K, bn):
     Xs, Ws, Ys, dYs = (as_seen_by_gpu(v, brg.BF16) for v in (X, W, Y, dY))
     desc = brg.FcDesc(N, C, K, bn, 16, 16)
     dX, dW, db = empty(d.x_shape, brg.BF16), empty(d.w_shape), empty((K,))
-    ws = torch.empty(N * K * 2, dtype=torch.uint8, device="cuda")
+    ws = workspace(N * K * 2)
     brg.brg_fc_bwd_chain(desc, brg.BF16, dev(dY, brg.BF16), dev(Y, brg.BF16), dev(X, brg.BF16), dev(W, brg.BF16),
                          brg.ACT_RELU, brg.ACT_RELU, dX, dW, db, ws)
     torch.cuda.synchronize()
     rX, rW, rb = orc.fc_bwd(d, dYs, Ys, Xs, Ws, orc.ACT_RELU, dx_bf16=True)
     check(host(dX), rX * (Xs > 0), brg.BF16, "masked dX")
-    check(host(dW), rW, brg.BF16, "dW")
-    check(host(db), rb, brg.BF16, "db")
+    check(host(dW), rW, brg.BF16, "dW", out=brg.F32)
+    check(host(db), rb, brg.BF16, "db", out=brg.F32)
     assert (host(dX) == 0).mean() > 0.3
+
+
+@pytest.mark.parametrize("knob,val", [("BRG_FC_GENERAL", "1"), ("BRG_FC_G64", "64"), ("BRG_FC_G64", "32"), ("BRG_NO_RING", "1"),
+                                      ("BRG_FC_G128", "0"), ("BRG_FC_WGT_GENERAL", "1")])
+@pytest.mark.parametrize("dtype,bc", [(brg.F32, 64), (brg.BF16, 16)])
+def test_fc_kernel_variants_forced(monkeypatch, knob, val, dtype, bc):
+    """Every override that moves a fully connected layer to another kernel: same results."""
+    monkeypatch.setenv(knob, val)
+    brg.brg_tuning_reload()
+    N, C, K = 256, 512, 256
+    rng = np.random.default_rng(len(knob) + int(val))
+    d = orc.FcShape(N, C, K, 64, bc, bc)
+    X, W = wl.uniform(rng, d.x_shape), wl.normal(rng, d.w_shape, (1.0 / C) ** 0.5)
+    b, dY = wl.normal(rng, (K,), 0.1), wl.uniform(rng, d.y_shape)
+    Xs, Ws, dYs = (as_seen_by_gpu(v, dtype) for v in (X, W, dY))
+    bf = dtype == brg.BF16
+    Y = _fwd(d, X, W, b, brg.ACT_RELU, dtype, dtype)
+    check(Y, orc.fc_fwd(d, Xs, Ws, b, orc.ACT_RELU, bf), dtype, "fwd")
+    dX, dW, db = _bwd(d, dY, None, X, W, brg.ACT_NONE, dtype)
+    rX, rW, rb = orc.fc_bwd(d, dYs, None, Xs, Ws, orc.ACT_NONE, dx_bf16=bf)
+    check(dX, rX, dtype, "dX")
+    check(dW, rW, dtype, "dW", out=brg.F32)
+    check(db, rb, dtype, "db", out=brg.F32)

@@ -8,7 +8,7 @@ import torch
 import oracle as orc
 import paper_1906_06440_amd as brg
 import workloads as wl
-from gpu_util import as_seen_by_gpu, check, dev, empty, host
+from gpu_util import as_seen_by_gpu, check, dev, empty, host, workspace
 
 pytestmark = pytest.mark.gpu
 
@@ -24,8 +24,8 @@ def test_graph_replay_matches_eager_conv_and_fc():
     O3 = empty((N, C // 16, H, H, 16), brg.BF16)
     G1 = empty((N, C // 16, H, H, 16), brg.BF16)
     ddO = dev(dO, brg.BF16)
-    ws1 = torch.empty(brg.brg_conv_ws_bytes(d1, brg.BF16), dtype=torch.uint8, device="cuda")
-    ws3 = torch.empty(brg.brg_conv_ws_bytes(d3, brg.BF16), dtype=torch.uint8, device="cuda")
+    ws1 = workspace(max(16, brg.brg_conv_ws_bytes(d1, brg.BF16)))
+    ws3 = workspace(max(16, brg.brg_conv_ws_bytes(d3, brg.BF16)))
     X0, Ws, bs, _ = wl.cfg3_mlp()
     fd = brg.FcDesc(1024, 1024, 1024, 64, 64, 64)
     X, Wf, bf, Y = dev(X0), dev(Ws[0]), dev(bs[0]), torch.empty((16, 16, 64, 64), device="cuda")
@@ -38,8 +38,8 @@ def test_graph_replay_matches_eager_conv_and_fc():
     gI16, gO16, gI16b, gO16b = dev(I16, brg.BF16), dev(dO16, brg.BF16), dev(I16b, brg.BF16), dev(dO16b, brg.BF16)
     gW1 = torch.empty((K // 16, C // 16, 1, 1, 16, 16), device="cuda")
     gW3 = torch.empty((C // 16, C // 16, 3, 3, 16, 16), device="cuda")
-    wsw1 = torch.empty(max(16, brg.brg_conv_bwd_wgt_ws_bytes(dw1, brg.BF16)), dtype=torch.uint8, device="cuda")
-    wsw3 = torch.empty(max(16, brg.brg_conv_bwd_wgt_ws_bytes(dw3, brg.BF16)), dtype=torch.uint8, device="cuda")
+    wsw1 = workspace(max(16, brg.brg_conv_bwd_wgt_ws_bytes(dw1, brg.BF16)))
+    wsw3 = workspace(max(16, brg.brg_conv_bwd_wgt_ws_bytes(dw3, brg.BF16)))
     assert wsw1.numel() > 16 and wsw3.numel() > 16, "these shapes should split the pixel range"
     gX, gW, gb = torch.empty_like(X), torch.empty_like(Wf), torch.empty(1024, device="cuda")
 
@@ -80,8 +80,8 @@ def test_graph_replay_matches_eager_lstm_forward_and_backward():
     h, s, g = empty((T, N, K)), empty((T, N, K)), empty((4, T, N, K))
     dh = dev(wl.uniform(np.random.default_rng(9), (T, N, K)))
     dx, dW, dR, db = empty((T, N, Cc)), empty(W4.shape), empty(R4.shape), empty((4, K))
-    ws_f = torch.zeros(64, dtype=torch.uint8, device="cuda")
-    ws_b = torch.empty(brg.brg_lstm_bwd_ws_bytes(desc), dtype=torch.uint8, device="cuda")
+    ws_f = workspace(64)
+    ws_b = workspace(max(16, brg.brg_lstm_bwd_ws_bytes(desc)))
 
     def work():
         brg.brg_lstm_fwd(desc, brg.F32, gx, gW4, gR4, gb4, None, None, h, s, g, ws_f)

@@ -6,9 +6,16 @@ import torch
 import oracle as orc
 import paper_1906_06440_amd as brg
 import workloads as wl
-from gpu_util import check, dev, empty, host
+from gpu_util import check, dev, empty, host, workspace
 
 pytestmark = pytest.mark.gpu
+
+
+def _bwd_widen(T):
+    """The gate gradients of step t carry the rounding errors of the T - t dependent steps before them (each an
+    fp32 GEMM plus element-wise products), and dW, dR, db sum them over all steps: the element-wise bound is
+    widened by sqrt(T), the growth of a sum of independent errors."""
+    return max(1.0, float(T) ** 0.5)
 
 
 def gpu_lstm(d, x, W4, R4, b4=None, h0=None, s0=None, want_gates=True, use_ws=True):
@@ -16,7 +23,7 @@ def gpu_lstm(d, x, W4, R4, b4=None, h0=None, s0=None, want_gates=True, use_ws=Tr
     h, s = empty((d.T, d.N, d.K)), empty((d.T, d.N, d.K))
     g = empty((4, d.T, d.N, d.K)) if want_gates else None
     opt = lambda a: None if a is None else dev(a)
-    ws = torch.zeros(64, dtype=torch.uint8, device="cuda") if use_ws else None   # grid-barrier words
+    ws = workspace(64) if use_ws else None   # grid-barrier words (cleared by the library)
     brg.brg_lstm_fwd(desc, brg.F32, dev(x), dev(W4), dev(R4), opt(b4), opt(h0), opt(s0), h, s, g, ws)
     torch.cuda.synchronize()
     if ws is not None:   # word 1 of the workspace: the resident kernel gave up waiting
@@ -85,18 +92,19 @@ def test_lstm_backward(T, N, C, K, bc, bk, full):
     db4 = empty((4, K)) if full else None
     dh0 = empty((N, K)) if full else None
     ds0 = empty((N, K)) if full else None
-    ws = torch.empty(brg.brg_lstm_bwd_ws_bytes(desc), dtype=torch.uint8, device="cuda")
+    ws = workspace(brg.brg_lstm_bwd_ws_bytes(desc))
     brg.brg_lstm_bwd(desc, brg.F32, dev(x), dev(W4), dev(R4), opt(h0), opt(s0), dev(h), dev(s), dev(g), dev(dh), opt(ds_last),
                      dx, dW4, dR4, db4, dh0, ds0, ws)
     torch.cuda.synchronize()
     rx, rW, rR, rb, rh0, rs0 = orc.lstm_bwd(d, x, W4, R4, h0, s0, h, s, g, dh, ds_last)
-    check(host(dx), rx, brg.F32, "dx")
-    check(host(dW4), rW, brg.F32, "dW4")
-    check(host(dR4), rR, brg.F32, "dR4")
+    wd = _bwd_widen(T)
+    check(host(dx), rx, brg.F32, "dx", widen=wd)
+    check(host(dW4), rW, brg.F32, "dW4", widen=wd)
+    check(host(dR4), rR, brg.F32, "dR4", widen=wd)
     if full:
-        check(host(db4), rb, brg.F32, "db4")
-        check(host(dh0), rh0, brg.F32, "dh0")
-        check(host(ds0), rs0, brg.F32, "ds0")
+        check(host(db4), rb, brg.F32, "db4", widen=wd)
+        check(host(dh0), rh0, brg.F32, "dh0", widen=wd)
+        check(host(ds0), rs0, brg.F32, "ds0", widen=wd)
 
 
 def test_config4_backward_full_size():
@@ -108,12 +116,27 @@ def test_config4_backward_full_size():
     dh = wl.uniform(rng, (50, 64, 1024), -0.1, 0.1)
     desc = brg.LstmDesc(50, 64, 1024, 1024, 16, 64, 64)
     dx, dW4, dR4, db4 = empty((50, 64, 1024)), empty(d.w_shape), empty(d.r_shape), empty((4, 1024))
-    ws = torch.empty(brg.brg_lstm_bwd_ws_bytes(desc), dtype=torch.uint8, device="cuda")
+    ws = workspace(brg.brg_lstm_bwd_ws_bytes(desc))
     brg.brg_lstm_bwd(desc, brg.F32, dev(x), dev(W4), dev(R4), None, None, dev(h), dev(s), dev(g), dev(dh), None,
                      dx, dW4, dR4, db4, None, None, ws)
     torch.cuda.synchronize()
     rx, rW, rR, rb, _, _ = orc.lstm_bwd(d, x, W4, R4, None, None, h, s, g, dh)
-    check(host(dx), rx, brg.F32, "dx")
-    check(host(dW4), rW, brg.F32, "dW4")
-    check(host(dR4), rR, brg.F32, "dR4")
-    check(host(db4), rb, brg.F32, "db4")
+    wd = _bwd_widen(50)
+    check(host(dx), rx, brg.F32, "dx", widen=wd)
+    check(host(dW4), rW, brg.F32, "dW4", widen=wd)
+    check(host(dR4), rR, brg.F32, "dR4", widen=wd)
+    check(host(db4), rb, brg.F32, "db4", widen=wd)
+
+
+def test_lstm_general_path_forced(monkeypatch):
+    """BRG_LSTM_GENERAL: a shape of the resident / batched kernels on one general launch per time step."""
+    monkeypatch.setenv("BRG_LSTM_GENERAL", "1")
+    brg.brg_tuning_reload()
+    T, N, C, K = 4, 64, 128, 128
+    x, W4, R4, b4 = wl.cfg4_lstm(T, N, C, K, 64, 64, with_bias=True, seed_extra=21)
+    d = orc.LstmShape(T, N, C, K, 16, 64, 64)
+    h, s, g = gpu_lstm(d, x, W4, R4, b4=b4)
+    rh, rs, rg = orc.lstm_fwd(d, x, W4, R4, b4=b4)
+    check(h, rh, brg.F32, "h (general)")
+    check(s, rs, brg.F32, "s (general)")
+    check(g, rg, brg.F32, "gates (general)")
