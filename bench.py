@@ -229,13 +229,15 @@ def make_cfg4_bwd():
     return fn, 2 * 50 * 2.0 * 64 * 4 * 1024 * 2048, "f32", "cfg4 backward: LSTM bwd (dx, dW, dR, db) T=50 N=64 C=K=1024, fp32"
 
 
-def make_cfg5_layers(N=64):
+def make_cfg5_layers(N=64, only=None):
     """Returns [(layer, fwd_fn, bwd_fn)] for the 23 distinct ResNet-50 v1.5 shapes, bf16 in/out."""
     import torch
     import paper_1906_06440_amd as brg
     import workloads as wl
     out = []
     for L in wl.resnet50_v15_layers():
+        if only and L.name not in only:
+            continue
         # the 3-channel stem is stored as one channel block of 4 (8 bytes per pixel), every other layer in blocks of 16
         bc = 4 if L.C < 16 else 16
         I, W, dO = wl.conv_tensors(N, L.C, L.H, L.K, L.R, L.stride, L.pad, bc=bc, cfg_index=5, want_dO=True)
@@ -256,12 +258,12 @@ def make_cfg5_layers(N=64):
     return out
 
 
-def run_cfg5(steps, warmup, N=64, use_graph=True, with_upd=False):
+def run_cfg5(steps, warmup, N=64, use_graph=True, with_upd=False, only=None):
     """Weighted efficiency (sum n_i F_i) / (sum n_i t_i) over the 53 layers, fwd and bwd-data (and, on request,
     the weight gradient).  Each layer's K timed calls are replayed from one
     HIP graph (see _time_graph) unless use_graph is False."""
     res = {}
-    layers = make_cfg5_layers(N)
+    layers = make_cfg5_layers(N, only)
     for name, sel in (("fwd", 1), ("bwd_data", 2)) + ((("bwd_wgt", 3),) if with_upd else ()):
         F = T = 0.0
         per = []
@@ -337,6 +339,7 @@ def main():
     ap.add_argument("--no-others", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="cfg5: time eager launches instead of a HIP graph replay")
     ap.add_argument("--upd", action="store_true", help="cfg5: also time the weight gradient")
+    ap.add_argument("--layers", default=None, help="cfg5: comma-separated layer names to run instead of all 23 shapes")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU only (no collectives, no sharding); run with --gpus 1",
@@ -366,7 +369,8 @@ def main():
 
     if args.workload == "cfg5":
         nb = args.batch or 64
-        r5 = run_cfg5(max(3, args.steps // 10), max(1, args.warmup // 5), N=nb, use_graph=not args.no_graph, with_upd=args.upd)
+        r5 = run_cfg5(max(3, args.steps // 10), max(1, args.warmup // 5), N=nb, use_graph=not args.no_graph, with_upd=args.upd,
+                      only=args.layers.split(",") if args.layers else None)
         tf = r5["fwd"]["weighted_tflops"]
         line = {"metric": "GFLOP/s and % of MI355X MFMA peak for BRGEMM conv/FC/LSTM on 1 GPU",
                 "value": tf * 1e3, "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

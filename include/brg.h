@@ -173,6 +173,21 @@ int brg_conv_bwd_wgt(const brg_conv_desc_t *desc, brg_dtype_t dtype, const void 
  * order.  With ws == NULL such a layer takes the general kernel. */
 int64_t brg_conv_bwd_wgt_ws_bytes(const brg_conv_desc_t *desc, brg_dtype_t dtype);
 
+/* brg_conv_bwd_wgt for callers that cannot allocate device memory or carry a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same planner, kernels and
+ * results as brg_conv_bwd_wgt given the workspace of brg_conv_bwd_wgt_ws_bytes, but the partial sums of
+ * the pixel ranges live in a device array built into the library (BRG_CONV_BWD_WGT_NOALLOC_MAX_BYTES,
+ * one copy per GPU, held until the process ends).  The call allocates and frees nothing.  A layer whose
+ * brg_conv_bwd_wgt_ws_bytes exceeds that size returns BRG_EUNSUPPORTED (validated on the host, before
+ * any GPU call); all 53 ResNet-50 layers at minibatch 64 fit.  The array keeps the previous call's
+ * contents and needs no clearing: every range is written in full before it is read.  All calls on one GPU
+ * share the array, so two calls that may overlap in time on the same GPU (different streams) race;
+ * calls on one stream, or on different GPUs, do not. */
+#define BRG_CONV_BWD_WGT_NOALLOC_MAX_BYTES (72 * 1024 * 1024)
+
+int brg_conv_bwd_wgt_noalloc(const brg_conv_desc_t *desc, brg_dtype_t dtype, const void *I,
+                             const void *dO, float *dWt, brg_stream_t stream);
+
 /* ---------------------------------------------------------------------------
  * Fully connected layer on blocked layouts (paper section 3.3, Algorithm 5):
  *

@@ -18,7 +18,7 @@ __all__ = [
     "ConvDesc", "FcDesc", "LstmDesc",
     "brg_gemm", "brg_gemm_strided", "brg_conv_ws_bytes", "brg_conv_fwd", "brg_conv_bwd_data", "brg_conv_bwd_wgt",
     "brg_conv_bwd_wgt_ws_bytes", "brg_fc_fwd", "brg_fc_bwd", "brg_fc_bwd_chain", "brg_lstm_fwd", "brg_lstm_bwd",
-    "brg_lstm_bwd_ws_bytes", "brg_tuning_reload", "EXPORTS",
+    "brg_lstm_bwd_ws_bytes", "brg_conv_bwd_wgt_noalloc", "brg_tuning_reload", "CONV_BWD_WGT_NOALLOC_MAX_BYTES", "EXPORTS",
 ]
 
 F32, BF16 = 0, 1
@@ -29,8 +29,9 @@ _STATUS = {0: "BRG_OK", 1: "BRG_EINVAL", 2: "BRG_EALIGN", 3: "BRG_EUNSUPPORTED",
 EXPORTS = [
     "brg_last_error", "brg_version", "brg_gemm", "brg_gemm_strided", "brg_conv_ws_bytes", "brg_conv_fwd",
     "brg_conv_bwd_data", "brg_conv_bwd_wgt", "brg_conv_bwd_wgt_ws_bytes", "brg_fc_fwd", "brg_fc_bwd", "brg_fc_bwd_chain",
-    "brg_lstm_fwd", "brg_lstm_bwd", "brg_lstm_bwd_ws_bytes", "brg_tuning_reload",
+    "brg_lstm_fwd", "brg_lstm_bwd", "brg_lstm_bwd_ws_bytes", "brg_conv_bwd_wgt_noalloc", "brg_tuning_reload",
 ]
+CONV_BWD_WGT_NOALLOC_MAX_BYTES = 72 * 1024 * 1024
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -81,6 +82,7 @@ def load():
     lib.brg_conv_bwd_data.argtypes = [C.POINTER(ConvDesc), ci, ci, vp, vp, vp, vp, vp]
     lib.brg_conv_bwd_wgt.argtypes = [C.POINTER(ConvDesc), ci, vp, vp, vp, vp, vp]
     lib.brg_conv_bwd_wgt_ws_bytes.argtypes = [C.POINTER(ConvDesc), ci]
+    lib.brg_conv_bwd_wgt_noalloc.argtypes = [C.POINTER(ConvDesc), ci, vp, vp, vp, vp]
     lib.brg_tuning_reload.argtypes = []
     lib.brg_tuning_reload.restype = None
     lib.brg_fc_fwd.argtypes = [C.POINTER(FcDesc), ci, ci, vp, vp, vp, ci, vp, vp]
@@ -168,6 +170,10 @@ def brg_conv_bwd_wgt_ws_bytes(desc: ConvDesc, dtype) -> int:
 def brg_conv_bwd_wgt(desc: ConvDesc, dtype, I, dO, dWt, ws=None, stream=None):
     _check(load().brg_conv_bwd_wgt(C.byref(desc), dtype, _ptr(I), _ptr(dO), _ptr(dWt), _ptr(ws),
                                    _stream(stream)))
+
+
+def brg_conv_bwd_wgt_noalloc(desc: ConvDesc, dtype, I, dO, dWt, stream=None):
+    _check(load().brg_conv_bwd_wgt_noalloc(C.byref(desc), dtype, _ptr(I), _ptr(dO), _ptr(dWt), _stream(stream)))
 
 
 def brg_tuning_reload():

@@ -1,6 +1,7 @@
 // Convolutions on blocked NCHWc / KCRSck layouts as batch-reduce chains
 // (paper section 3.2, Algorithm 4): the address lists over (c-block, r, s) are
 // index arithmetic inside the kernel, padding is logical.
+#include <atomic>
 #include <cstdlib>
 
 #include "brg_engine.hpp"
@@ -1034,6 +1035,60 @@ extern "C" int brg_conv_bwd_wgt(const brg_conv_desc_t *desc, brg_dtype_t dtype, 
     if (dtype == BRG_F32 && !(wp.ok && (wp.nsplit == 1 || ws))) return conv_bwd_wgt_launch<float>(d, I, dO, dWt, s);
     if (wp.ok && (wp.nsplit == 1 || ws)) return conv_wgt_bf16_launch(wp, d.N, d.Cb, d.Kb, d.H, d.W, d.sh, I, dO, dWt, ws, s);
     return conv_bwd_wgt_launch<bf16_t>(d, I, dO, dWt, s);
+}
+
+// ---- the weight gradient for callers that cannot allocate --------------------------------------
+// The partial sums of the pixel ranges go to a file-scope device array instead of a caller workspace.
+// Every GPU holds its own copy of the array at its own address; that address is asked for once per
+// device, with the device current, and kept.
+static __device__ __align__(256) unsigned char wgt_scratch[BRG_CONV_BWD_WGT_NOALLOC_MAX_BYTES];
+
+namespace brg {
+constexpr int WGT_SCRATCH_MAXDEV = 64;
+static std::atomic<void *> wgt_scratch_addr[WGT_SCRATCH_MAXDEV];
+
+static int wgt_scratch_for_current_device(void **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(BRG_EHIP, "brg_conv_bwd_wgt_noalloc: hipGetDevice: %s", hipGetErrorString(e));
+    BRG_REQUIRE(dev >= 0 && dev < WGT_SCRATCH_MAXDEV, BRG_EUNSUPPORTED, "brg_conv_bwd_wgt_noalloc: device index %d", dev);
+    void *p = wgt_scratch_addr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(wgt_scratch));
+        if (e != hipSuccess || !p)
+            return fail(BRG_EHIP, "brg_conv_bwd_wgt_noalloc: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        wgt_scratch_addr[dev].store(p, std::memory_order_release);   // (two threads racing here store the same address)
+    }
+    *out = p;
+    return BRG_OK;
+}
+}  // namespace brg
+
+extern "C" int brg_conv_bwd_wgt_noalloc(const brg_conv_desc_t *desc, brg_dtype_t dtype, const void *I,
+                                        const void *dO, float *dWt, brg_stream_t stream)
+{
+    using namespace brg;
+    ConvDims d;
+    int rc = conv_dims(desc, &d, "brg_conv_bwd_wgt_noalloc");
+    if (rc) return rc;
+    BRG_REQUIRE(valid_dtype(dtype), BRG_EINVAL, "brg_conv_bwd_wgt_noalloc: bad dtype");
+    BRG_REQUIRE(I && dO && dWt, BRG_EINVAL, "brg_conv_bwd_wgt_noalloc: null tensor");
+    BRG_REQUIRE(aligned16(I) && aligned16(dO) && aligned16(dWt), BRG_EALIGN,
+                "brg_conv_bwd_wgt_noalloc: pointer not 16-byte aligned");
+    const int64_t need = brg_conv_bwd_wgt_ws_bytes(desc, dtype);
+    BRG_REQUIRE(need <= BRG_CONV_BWD_WGT_NOALLOC_MAX_BYTES, BRG_EUNSUPPORTED,
+                "brg_conv_bwd_wgt_noalloc: this layer needs %lld bytes of partial sums, the built-in scratch holds %lld",
+                (long long)need, (long long)BRG_CONV_BWD_WGT_NOALLOC_MAX_BYTES);
+    void *scratch = nullptr;
+    if (need > 0) {
+        rc = wgt_scratch_for_current_device(&scratch);
+        if (rc) return rc;
+    }
+    // Same planner and kernels as brg_conv_bwd_wgt.  Every range writes its whole partial result before the
+    // range sum reads it, so nothing in the scratch has to start at zero and the previous call's contents
+    // are simply overwritten.
+    return brg_conv_bwd_wgt(desc, dtype, I, dO, dWt, scratch, stream);
 }
 
 extern "C" int64_t brg_conv_bwd_wgt_ws_bytes(const brg_conv_desc_t *desc, brg_dtype_t dtype)
