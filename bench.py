@@ -123,6 +123,33 @@ def make_cfg1():
     return fn, 2.0 * 64 * 64 * 64 * 16, "f32", "cfg1: one BRGEMM, 16 x (64x64x64), fp32"
 
 
+def make_cfg1_ptrs():
+    """cfg1 in the address-list form of section 2 (two device arrays of 16 block pointers, scrambled order)."""
+    import numpy as np
+    import torch
+    import paper_1906_06440_amd as brg
+    import workloads as wl
+    A, B = wl.cfg1_brgemm()
+    dA, dB, dC = _dev(A), _dev(B), torch.empty((64, 64), device="cuda")
+    perm = np.random.default_rng(1).permutation(16)
+    ap = torch.tensor([dA.data_ptr() + int(i) * 4096 * 4 for i in perm], dtype=torch.int64, device="cuda")
+    bp = torch.tensor([dB.data_ptr() + int(i) * 4096 * 4 for i in perm], dtype=torch.int64, device="cuda")
+    fn = lambda: brg.brg_gemm(brg.F32, brg.F32, 64, 64, 64, 64, 64, 64, ap, bp, dC, 16)
+    fn.keep = (dA, dB)
+    return fn, 2.0 * 64 * 64 * 64 * 16, "f32", "cfg1 as an address list: one BRGEMM, 16 x (64x64x64) block pointers, fp32"
+
+
+def make_cfg1_bf16():
+    """cfg1's chain with bf16 blocks and fp32 result (strided form)."""
+    import torch
+    import paper_1906_06440_amd as brg
+    import workloads as wl
+    A, B = wl.cfg1_brgemm()
+    dA, dB, dC = _dev(A, True), _dev(B, True), torch.empty((64, 64), device="cuda")
+    fn = lambda: brg.brg_gemm_strided(brg.BF16, brg.F32, 64, 64, 64, 64, 64, 64, dA, 4096, dB, 4096, dC, 16)
+    return fn, 2.0 * 64 * 64 * 64 * 16, "bf16", "cfg1 in bf16: one BRGEMM, 16 x (64x64x64), bf16 in, fp32 out"
+
+
 def make_cfg2(N=64):
     import torch
     import paper_1906_06440_amd as brg
@@ -291,7 +318,7 @@ def run_cfg5(steps, warmup, N=64, use_graph=True, with_upd=False, only=None):
     return res
 
 
-MAKERS = {"cfg1": make_cfg1, "cfg2": make_cfg2, "cfg3": make_cfg3, "cfg4": make_cfg4, "cfg3_bf16": make_cfg3_bf16, "cfg4_bwd": make_cfg4_bwd}
+MAKERS = {"cfg1": make_cfg1, "cfg1_ptrs": make_cfg1_ptrs, "cfg1_bf16": make_cfg1_bf16, "cfg2": make_cfg2, "cfg3": make_cfg3, "cfg4": make_cfg4, "cfg3_bf16": make_cfg3_bf16, "cfg4_bwd": make_cfg4_bwd}
 
 
 def cpu_baseline_cfg2():
@@ -331,7 +358,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "cfg3_bf16", "cfg4_bwd", "copy"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg1_ptrs", "cfg1_bf16", "cfg2", "cfg3", "cfg4", "cfg5", "cfg3_bf16", "cfg4_bwd", "copy"])
     ap.add_argument("--batch", type=int, default=None,
                     help="minibatch of cfg2 / cfg3 / cfg5 instead of the configured one (context rows: the paper's own "
                          "28 / 1344, inference at 1); such a line carries no others and no cpu_baseline")
@@ -405,7 +432,7 @@ def main():
     }
     if not args.no_others:
         others = {}
-        for key in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg3_bf16", "cfg4_bwd"):
+        for key in ("cfg1", "cfg1_ptrs", "cfg1_bf16", "cfg2", "cfg3", "cfg4", "cfg3_bf16", "cfg4_bwd"):
             if key == args.workload:
                 continue
             f2, fl2, dt2, nm2 = MAKERS[key]()

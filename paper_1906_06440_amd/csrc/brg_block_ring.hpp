@@ -10,6 +10,13 @@
 // instructions, the first fragments of the next stage are read right behind it, and the buffer it frees
 // is refilled at once with the stage four steps ahead (three stages, about 6000 matrix-pipe clocks, in
 // flight).  Row-fast operands are read with one ds_read_b64 per k step over interleaved MFMA tiles.
+//
+// PTRS: the address-list form of section 2 of the paper ("two arrays of pointers").  Block i of the chain is
+// A_ptrs[i] / B_ptrs[i] (device arrays), read with scalar loads one ring turn ahead of the stage that needs
+// them.  Direct loads need 16-byte aligned rows and the arrays cannot be inspected from the host without a
+// synchronisation, so every wave first scans the whole list; if any block (or a leading dimension) is less
+// aligned, all stages are filled through registers instead (four element loads and one 16-byte LDS store
+// per piece, placed exactly where the direct load would have put it).
 #pragma once
 
 #include "brg_block_dma.hpp"
@@ -20,7 +27,7 @@ namespace brg {
 constexpr int BR_STAGE = 2 * BD_OPER;                              // floats: A block, B block
 constexpr size_t BR_SMEM = 4 * BR_STAGE * sizeof(float);           // 128 KiB: four stages
 
-template <bool AKF, bool BKF> __global__ __launch_bounds__(512) void block_ring_f32(BlockTileArgs a)
+template <bool AKF, bool BKF, bool PTRS = false> __global__ __launch_bounds__(512) void block_ring_f32(BlockTileArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) float br_smem[];   // the only LDS object: starts at byte 0
     const int t = threadIdx.x, lane = t & 63;
@@ -50,8 +57,9 @@ template <bool AKF, bool BKF> __global__ __launch_bounds__(512) void block_ring_
 
     // ---- direct loads: wave wv moves rows 8 wv .. 8 wv + 7 of both blocks, 4 rows per instruction.  Lane L
     // sits at row r = r0 + L/16, piece position L%16, and fetches the logical piece (L%16) ^ (r & 15).
-    const float *gA = a.A + tm * a.a_tile;
-    const float *gB = a.B + tn * a.b_tile;
+    const int64_t a_toff = tm * a.a_tile, b_toff = tn * a.b_tile;
+    const float *gA = PTRS ? nullptr : a.A + a_toff;
+    const float *gB = PTRS ? nullptr : a.B + b_toff;
     int ga_off[2], gb_off[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -60,14 +68,42 @@ template <bool AKF, bool BKF> __global__ __launch_bounds__(512) void block_ring_
         ga_off[j] = r * a.a_ld + piece * 4;
         gb_off[j] = r * a.b_ld + piece * 4;
     }
+    bool direct = true;
+    if (PTRS) {
+        unsigned bad = (unsigned)((a.a_ld | a.b_ld) & 3) | (unsigned)((a_toff | b_toff) & 3);
+        for (int i = lane; i < chain; i += 64)
+            bad |= (unsigned)(((uintptr_t)a.A_ptrs[i] | (uintptr_t)a.B_ptrs[i]) & 15u);
+        direct = __builtin_amdgcn_ballot_w64(bad != 0u) == 0ull;      // the same answer in every wave
+    }
     float *const ldsA = br_smem + 8 * wv * 64;
 #define BR_ISSUE(I, BUF)                                                                               \
     {                                                                                                  \
-        const float *pa_ = gA + (int64_t)(I) * a_chain, *pb_ = gB + (int64_t)(I) * b_chain;           \
-        _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                  \
-        {                                                                                              \
-            __builtin_amdgcn_global_load_lds(pa_ + ga_off[j], ldsA + (BUF) * BR_STAGE + j * 256, 16, 0, 0);           \
-            __builtin_amdgcn_global_load_lds(pb_ + gb_off[j], ldsA + (BUF) * BR_STAGE + BD_OPER + j * 256, 16, 0, 0); \
+        const float *pa_, *pb_;                                                                        \
+        if (PTRS) {                                                                                    \
+            pa_ = a.A_ptrs[I] + a_toff;                                                                \
+            pb_ = a.B_ptrs[I] + b_toff;                                                                \
+        } else {                                                                                       \
+            pa_ = gA + (int64_t)(I) * a_chain;                                                         \
+            pb_ = gB + (int64_t)(I) * b_chain;                                                         \
+        }                                                                                              \
+        if (!PTRS || direct) {                                                                         \
+            _Pragma("unroll") for (int j = 0; j < 2; ++j)                                              \
+            {                                                                                          \
+                __builtin_amdgcn_global_load_lds(pa_ + ga_off[j], ldsA + (BUF) * BR_STAGE + j * 256, 16, 0, 0);           \
+                __builtin_amdgcn_global_load_lds(pb_ + gb_off[j], ldsA + (BUF) * BR_STAGE + BD_OPER + j * 256, 16, 0, 0); \
+            }                                                                                          \
+        } else {                                                                                       \
+            _Pragma("unroll") for (int j = 0; j < 2; ++j)                                              \
+            {                                                                                          \
+                float4v va_, vb_;                                                                      \
+                _Pragma("unroll") for (int e = 0; e < 4; ++e)                                          \
+                {                                                                                      \
+                    va_[e] = pa_[ga_off[j] + e];                                                       \
+                    vb_[e] = pb_[gb_off[j] + e];                                                       \
+                }                                                                                      \
+                *(float4v *)(ldsA + (BUF) * BR_STAGE + j * 256 + lane * 4) = va_;                      \
+                *(float4v *)(ldsA + (BUF) * BR_STAGE + BD_OPER + j * 256 + lane * 4) = vb_;            \
+            }                                                                                          \
         }                                                                                              \
     }
 
@@ -122,6 +158,7 @@ template <bool AKF, bool BKF> __global__ __launch_bounds__(512) void block_ring_
     } else {
         asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
     }
+    if (PTRS) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // (register-staged pieces: the LDS stores have landed)
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 
@@ -220,11 +257,11 @@ template <bool AKF, bool BKF> __global__ __launch_bounds__(512) void block_ring_
 }
 
 // chains shorter than the ring go to the double-buffered kernel
-template <bool A_KFAST, bool B_KFAST> static int launch_block_ring(BlockTileArgs &a, hipStream_t s, const char *who)
+template <bool A_KFAST, bool B_KFAST, bool PTRS = false> static int launch_block_ring(BlockTileArgs &a, hipStream_t s, const char *who)
 {
-    if (a.chain < 4 || knobs().no_ring.set) return launch_block_dma<A_KFAST, B_KFAST>(a, s, who);
+    if (!PTRS && (a.chain < 4 || knobs().no_ring.set)) return launch_block_dma<A_KFAST, B_KFAST>(a, s, who);
     a.xcd_patch = (a.tiles_m == 16 && a.tiles_n == 16) ? 1 : 0;
-    auto kern = block_ring_f32<A_KFAST, B_KFAST>;
+    auto kern = block_ring_f32<A_KFAST, B_KFAST, PTRS>;
     static thread_local int allowed_on = -1;
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);

@@ -1,11 +1,15 @@
 // brg_gemm / brg_gemm_strided: the batch-reduce GEMM of section 2 of the paper,
 //   C = act(beta*C + alpha * sum_i A_i*B_i + bias),
-// for arbitrary m, n, k and leading dimensions, on the general tile engine.
+// for arbitrary m, n, k and leading dimensions.  Chains of 64-deep blocks with m and n multiples of 64 --
+// the shape of config 1 and of every block call of the fully connected and LSTM layers -- run on the staged
+// kernels: fp32 on the four-stage ring (brg_block_ring.hpp), bf16 on the bf16 matrix instruction
+// (brg_h64.hpp), in the strided AND in the address-list form.  Everything else takes the general tile engine.
 #include <cstdlib>
 
 #include "brg_block_dma.hpp"
 #include "brg_block_ring.hpp"
 #include "brg_engine.hpp"
+#include "brg_h64.hpp"
 
 namespace brg {
 
@@ -95,8 +99,10 @@ static int launch_gemm(int64_t m, int64_t n, int64_t k, int64_t lda, int64_t ldb
     p.C = (TOut *)C;
     p.alpha = alpha; p.beta = beta; p.bias = bias; p.act = act;
     p.tiles_m = (int)((m + ENG_TM - 1) / ENG_TM);
-    int64_t tiles_n = (n + ENG_TN - 1) / ENG_TN;
-    dim3 grid((unsigned)(p.tiles_m * tiles_n));
+    const int64_t tiles_n = (n + ENG_TN - 1) / ENG_TN;
+    BRG_REQUIRE((int64_t)p.tiles_m * tiles_n < (1ll << 31), BRG_EINVAL, "brg_gemm: %lld x %lld tiles exceed the grid limit",
+                (long long)p.tiles_m, (long long)tiles_n);
+    dim3 grid((unsigned)((int64_t)p.tiles_m * tiles_n));
     hipLaunchKernelGGL((engine_kernel<GemmProb<TIn, TOut, PTRS>>), grid, dim3(256), 0, stream, p);
     return check_launch("brg_gemm launch");
 }
@@ -127,16 +133,33 @@ static int gemm_common(int dtype, int out_dtype, int64_t m, int64_t n, int64_t k
     if (m == 0 || n == 0) return BRG_OK;
     if (count == 0 || k == 0) count = 0;
     hipStream_t s = (hipStream_t)stream;
-    // 64 x 64 x 64 fp32 blocks at fixed strides: the dedicated block kernel
-    if (!ptrs && dtype == BRG_F32 && out_dtype == BRG_F32 && count > 0 && k == 64 && m % 64 == 0 && n % 64 == 0 &&
-        lda % 4 == 0 && ldb % 4 == 0 && ldc % 4 == 0 && strideA % 4 == 0 && strideB % 4 == 0 &&
-        lda < (1 << 24) && ldb < (1 << 24) && ldc < (1 << 24) && !knobs().gemm_general.set) {
+    const bool blocks64 = count > 0 && k == 64 && m % 64 == 0 && n % 64 == 0 && ldc % 4 == 0 && lda < (1 << 24) &&
+                          ldb < (1 << 24) && ldc < (1 << 24) && (m / 64) * (n / 64) < (1ll << 31) && !knobs().gemm_general.set;
+    // 64 x 64 x 64 fp32 blocks: the ring kernel.  Strided form: rows must be 16-byte aligned (decided here);
+    // address-list form: chains of at least four blocks, alignment decided inside the kernel.
+    if (blocks64 && dtype == BRG_F32 && out_dtype == BRG_F32 &&
+        (ptrs ? count >= 4 : (lda % 4 == 0 && ldb % 4 == 0 && strideA % 4 == 0 && strideB % 4 == 0))) {
         BlockTileArgs a = {};
         a.A = (const float *)A; a.B = (const float *)B; a.C = (float *)C; a.bias = bias; a.act = act;
+        a.A_ptrs = (const float *const *)A_ptrs; a.B_ptrs = (const float *const *)B_ptrs;
         a.tiles_m = (int)(m / 64); a.tiles_n = (int)(n / 64); a.chain = (int)count; a.alpha = alpha; a.beta = beta;
         a.a_tile = 64; a.a_chain = strideA; a.b_tile = 64 * ldb; a.b_chain = strideB;
         a.c_tile_m = 64; a.c_tile_n = 64 * ldc; a.a_ld = (int)lda; a.b_ld = (int)ldb; a.c_ld = (int)ldc;
+        if (ptrs) return launch_block_ring<false, true, true>(a, s, "brg_gemm launch");
         return launch_block_ring<false, true>(a, s, "brg_gemm_strided launch");
+    }
+    // 64 x 64 x 64 bf16 blocks: the bf16 matrix-instruction kernel (A blocks through the transposing LDS read)
+    if (blocks64 && dtype == BRG_BF16 &&
+        (ptrs || (lda % 8 == 0 && ldb % 8 == 0 && strideA % 8 == 0 && strideB % 8 == 0))) {
+        H64Args a = {};
+        a.A = (const bf16_t *)A; a.B = (const bf16_t *)B; a.C = C; a.bias = bias; a.act = act;
+        a.A_ptrs = (const bf16_t *const *)A_ptrs; a.B_ptrs = (const bf16_t *const *)B_ptrs;
+        a.tiles_m = (int)(m / 64); a.tiles_n = (int)(n / 64); a.chain = (int)count; a.alpha = alpha; a.beta = beta;
+        a.a_tile = 64; a.a_chain = strideA; a.b_tile = 64 * ldb; a.b_chain = strideB;
+        a.c_tile_m = 64; a.c_tile_n = 64 * ldc; a.a_ld = (int)lda; a.b_ld = (int)ldb; a.c_ld = (int)ldc;
+        const char *who = ptrs ? "brg_gemm (bf16) launch" : "brg_gemm_strided (bf16) launch";
+        if (out_dtype == BRG_F32) return ptrs ? launch_h64<false, true, true, float>(a, s, who) : launch_h64<false, true, false, float>(a, s, who);
+        return ptrs ? launch_h64<false, true, true, bf16_t>(a, s, who) : launch_h64<false, true, false, bf16_t>(a, s, who);
     }
 #define BRG_GEMM_GO(TI, TO)                                                                         \
     return ptrs ? launch_gemm<TI, TO, true>(m, n, k, lda, ldb, ldc, A_ptrs, B_ptrs, A, strideA, B,  \

@@ -112,3 +112,67 @@ def test_cfg1_on_the_other_kernels(monkeypatch, knob):
     want = np.zeros((64, 64), np.float32)
     orc.brgemm(list(A), list(B), 64, 64, 64, 64, 64, 64, want)
     check(_run_strided(A, B, 64, 64, 64, 64, 64, 64, 16, 4096, 4096), want, brg.F32, "cfg1 " + knob)
+
+
+def _ptr_list_case(dtype, out, m, n, k, count, lda, ldb, ldc, elem_off, alpha, beta, with_bias, act, seed):
+    """Blocks scattered through two big buffers at offsets that are multiples of `elem_off` elements (1 = only
+    element alignment), listed in a scrambled order, some blocks listed twice (blocks may repeat and alias)."""
+    rng = np.random.default_rng(seed)
+    esz = 2 if dtype == brg.BF16 else 4
+    span_a, span_b = lda * k + 24, ldb * n + 24
+    nblk = count + 3
+    Abuf = (2 * rng.random(nblk * span_a + 64, dtype=np.float32) - 1)
+    Bbuf = (2 * rng.random(nblk * span_b + 64, dtype=np.float32) - 1)
+    pick = rng.integers(0, nblk, count)
+    offa = [int(i) * span_a + int(rng.integers(0, 6)) * elem_off for i in pick]
+    offb = [int(i) * span_b + int(rng.integers(0, 6)) * elem_off for i in rng.permutation(pick)]
+    C0 = (2 * rng.random((n, ldc), dtype=np.float32) - 1)
+    bias = (2 * rng.random(m, dtype=np.float32) - 1) if with_bias else None
+    dA, dB = dev(Abuf, dtype), dev(Bbuf, dtype)
+    ap = torch.tensor([dA.data_ptr() + o * esz for o in offa], dtype=torch.int64, device="cuda")
+    bp = torch.tensor([dB.data_ptr() + o * esz for o in offb], dtype=torch.int64, device="cuda")
+    dC = empty((n, ldc), out)
+    dC.copy_(dev(C0, out))
+    brg.brg_gemm(dtype, out, m, n, k, lda, ldb, ldc, ap, bp, dC, count, alpha, beta, None if bias is None else dev(bias), act)
+    torch.cuda.synchronize()
+    got = host(dC)
+    Af, Bf = as_seen_by_gpu(Abuf, dtype), as_seen_by_gpu(Bbuf, dtype)
+    want = as_seen_by_gpu(C0, out).copy()
+    orc.brgemm([Af[o:] for o in offa], [Bf[o:] for o in offb], m, n, k, lda, ldb, ldc, want, alpha, beta, bias, act,
+               out == brg.BF16)
+    check(got[:, :m], want[:, :m], dtype, "pointer list %dx%dx%dx%d off %d" % (m, n, k, count, elem_off), out)
+    assert np.array_equal(got[:, m:], as_seen_by_gpu(C0, out)[:, m:]), "rows of C between m and ldc are never written"
+
+
+@pytest.mark.parametrize("dtype,out", [(brg.F32, brg.F32), (brg.BF16, brg.F32), (brg.BF16, brg.BF16)])
+@pytest.mark.parametrize("m,n,count,lda,ldb,ldc,elem_off", [
+    (64, 64, 16, 64, 64, 64, 8),        # cfg1's shape as an address list, 16-byte aligned blocks: direct loads
+    (128, 192, 6, 136, 72, 132, 8),     # several tiles, padded leading dimensions, aligned
+    (64, 128, 5, 64, 64, 64, 1),        # blocks with only element alignment: staged through registers
+    (128, 64, 7, 129, 67, 128, 1),      # leading dimensions that break row alignment as well
+    (64, 64, 2, 64, 64, 64, 8),         # short list (fp32: below the ring depth, general kernel)
+])
+def test_pointer_list_on_the_staged_kernels(dtype, out, m, n, count, lda, ldb, ldc, elem_off):
+    """brg_gemm (the paper's two pointer arrays) with 64-deep blocks, m and n multiples of 64: the staged kernels."""
+    _ptr_list_case(dtype, out, m, n, 64, count, lda, ldb, ldc, elem_off, 1.0, 0.0, False, brg.ACT_NONE, seed=m + n + count)
+    _ptr_list_case(dtype, out, m, n, 64, count, lda, ldb, ldc, elem_off, 0.75, -0.5, True, brg.ACT_RELU, seed=m + n + count + 1)
+
+
+@pytest.mark.parametrize("out", [brg.F32, brg.BF16])
+@pytest.mark.parametrize("m,n,count,lda,ldb,ldc", [(64, 64, 16, 64, 64, 64), (256, 128, 3, 264, 64, 256), (64, 320, 1, 64, 80, 68),
+                                                   (1024, 1024, 16, 1024, 64, 1024)])
+def test_bf16_strided_blocks_on_the_bf16_matrix_instruction(out, m, n, count, lda, ldb, ldc):
+    """brg_gemm_strided, bf16, 64-deep blocks (the first shape is cfg1's chain in bf16; the last a 1024-cubed GEMM
+    as 16 blocks): plain, and with alpha, beta, bias and an activation."""
+    k = 64
+    rng = np.random.default_rng(m + n + count)
+    sa, sb = lda * k + 8, ldb * n + 16
+    A = (2 * rng.random(count * sa, dtype=np.float32) - 1)
+    B = (2 * rng.random(count * sb, dtype=np.float32) - 1)
+    C0 = (2 * rng.random((n, ldc), dtype=np.float32) - 1)
+    bias = (2 * rng.random(m, dtype=np.float32) - 1)
+    for alpha, beta, b, act in [(1.0, 0.0, None, brg.ACT_NONE), (0.5, -1.5, bias, brg.ACT_TANH)]:
+        got = _run_strided(A, B, m, n, k, lda, ldb, ldc, count, sa, sb, brg.BF16, out, alpha, beta, C0, b, act)
+        want = _oracle_strided(A, B, m, n, k, lda, ldb, ldc, count, sa, sb, brg.BF16, out, alpha, beta, C0, b, act)
+        check(got[:, :m], want[:, :m], brg.BF16, f"bf16 {m}x{n}x{k}x{count}", out)
+        assert np.array_equal(got[:, m:], as_seen_by_gpu(C0, out)[:, m:])
