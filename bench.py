@@ -234,6 +234,24 @@ def make_cfg4():
     return fn, 50 * 2.0 * 64 * 4 * 1024 * 2048, "f32", "cfg4: LSTM fwd T=50 N=64 C=K=1024, fp32"
 
 
+def make_cfg4_variant(N=64, bf16=False):
+    """Context rows of the LSTM layer: the paper's own minibatch (N = 168, section 4.1.1) and bf16 operands."""
+    import torch
+    import paper_1906_06440_amd as brg
+    import workloads as wl
+    x, W4, R4, _ = wl.cfg4_lstm(50, N)
+    dt = brg.BF16 if bf16 else brg.F32
+    dx, dW, dR = _dev(x, bf16), _dev(W4, bf16), _dev(R4, bf16)
+    h = torch.empty((50, N, 1024), device="cuda", dtype=torch.bfloat16 if bf16 else torch.float32)
+    s = torch.empty((50, N, 1024), device="cuda")
+    g = torch.empty((4, 50, N, 1024), device="cuda")
+    desc = brg.LstmDesc(50, N, 1024, 1024, 16, 64, 64)
+    ws = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    fn = lambda: brg.brg_lstm_fwd(desc, dt, dx, dW, dR, None, None, None, h, s, g, ws)
+    fn.verify = lambda: _lstm_completed(ws, h)
+    return fn, 50 * 2.0 * N * 4 * 1024 * 2048, "bf16" if bf16 else "f32", "LSTM fwd T=50 N=%d C=K=1024, %s" % (N, "bf16 operands, fp32 state" if bf16 else "fp32")
+
+
 def make_cfg4_bwd():
     """Context row: backward pass of the cfg4 LSTM layer (dx, dW, dR, db from a random dh), fp32; the forward
     results it differentiates are computed once outside the timed region.  Flops: twice the forward's."""
@@ -318,7 +336,8 @@ def run_cfg5(steps, warmup, N=64, use_graph=True, with_upd=False, only=None):
     return res
 
 
-MAKERS = {"cfg1": make_cfg1, "cfg1_ptrs": make_cfg1_ptrs, "cfg1_bf16": make_cfg1_bf16, "cfg2": make_cfg2, "cfg3": make_cfg3, "cfg4": make_cfg4, "cfg3_bf16": make_cfg3_bf16, "cfg4_bwd": make_cfg4_bwd}
+MAKERS = {"cfg4_bf16": lambda: make_cfg4_variant(64, True), "cfg4_n168": lambda: make_cfg4_variant(168, False),
+          "cfg4_n168_bf16": lambda: make_cfg4_variant(168, True), "cfg1": make_cfg1, "cfg1_ptrs": make_cfg1_ptrs, "cfg1_bf16": make_cfg1_bf16, "cfg2": make_cfg2, "cfg3": make_cfg3, "cfg4": make_cfg4, "cfg3_bf16": make_cfg3_bf16, "cfg4_bwd": make_cfg4_bwd}
 
 
 def cpu_baseline_cfg2():
@@ -358,7 +377,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg1_ptrs", "cfg1_bf16", "cfg2", "cfg3", "cfg4", "cfg5", "cfg3_bf16", "cfg4_bwd", "copy"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg1_ptrs", "cfg1_bf16", "cfg2", "cfg3", "cfg4", "cfg5", "cfg3_bf16", "cfg4_bwd", "cfg4_bf16", "cfg4_n168",
+                             "cfg4_n168_bf16", "copy"])
     ap.add_argument("--batch", type=int, default=None,
                     help="minibatch of cfg2 / cfg3 / cfg5 instead of the configured one (context rows: the paper's own "
                          "28 / 1344, inference at 1); such a line carries no others and no cpu_baseline")
@@ -432,11 +452,11 @@ def main():
     }
     if not args.no_others:
         others = {}
-        for key in ("cfg1", "cfg1_ptrs", "cfg1_bf16", "cfg2", "cfg3", "cfg4", "cfg3_bf16", "cfg4_bwd"):
+        for key in ("cfg1", "cfg1_ptrs", "cfg1_bf16", "cfg2", "cfg3", "cfg4", "cfg3_bf16", "cfg4_bwd", "cfg4_bf16", "cfg4_n168", "cfg4_n168_bf16"):
             if key == args.workload:
                 continue
             f2, fl2, dt2, nm2 = MAKERS[key]()
-            st, wu = (30, 5) if key in ("cfg4", "cfg4_bwd") else (100, 10)
+            st, wu = (30, 5) if key.startswith("cfg4") else (100, 10)
             _, d2 = _time_steps(f2, st, wu)
             if hasattr(f2, "verify"):
                 f2.verify()

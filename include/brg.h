@@ -246,20 +246,25 @@ int brg_fc_bwd_chain(const brg_fc_desc_t *desc, brg_dtype_t dtype, const void *d
  *   W4: four [K/bk][C/bc][bc][bk] matrices back to back;  R4: four [K/bk][K/bk][bk][bk]
  *   x: [T][N][C];  b4: fp32 [4][K] or NULL;  h0, s0: [N][K] or NULL (zeros)
  *   outputs h, s: [T][N][K];  gates: [4][T][N][K] post-activation, or NULL
- * fp32 only in this build (dtype BRG_BF16 -> BRG_EUNSUPPORTED).
+ * Element types.  dtype BRG_F32: everything fp32.  dtype BRG_BF16 (the paper's kernel is "agnostic of the
+ * compute precision", section 2; it gives no recipe for the recurrence, this is the one built): the tensors that
+ * enter matrix products -- x, W4, R4, h0 and the result h -- are bf16, everything else (b4, s0, s, gates) is
+ * fp32; accumulation is fp32; h_t is rounded to bf16 (nearest even) once, when it is stored, and that stored
+ * value is what step t+1 multiplies; the cell state is carried in fp32.
  * The gate non-linearities and the state update run on the accumulators before
  * anything is stored.  `bn` is advisory (the kernel picks its own batch tile).
  *
  * Workspace: `ws` is NULL or DEVICE memory of at least 16 bytes, 16-byte aligned, whose
- * contents need no initialisation (the library clears it on the stream).  With bc = bk = 64,
- * T*N a multiple of 64, N <= 64, K/4 <= the number of compute units and BOTH `gates` and `ws`
- * given, the layer runs as four batch-reduce GEMMs for the input projections of all time steps
- * followed by ONE resident kernel for the recurrence, whose workgroups meet at a counter in
- * ws (32-bit word 0) once per time step.  The wait is bounded: if the workgroups cannot all be
- * resident for that long (another stream occupying the device), the kernel stops early, sets
- * the 32-bit word 1 of ws to a non-zero value and leaves h, s, gates undefined; a caller that
- * shares the device between streams should read that word after the stream has drained.
- * Without `gates` or `ws` (or for other shapes) every time step is a launch of its own.
+ * contents need no initialisation (the library clears both words on the stream, on every path).  With
+ * bc = bk = 64, N <= 256, K/4 <= the number of compute units and BOTH `gates` and `ws`
+ * given, the layer runs as batch-reduce GEMMs for the input projections of all time steps (T*N need not be a
+ * multiple of the tile) followed by ONE resident kernel for the recurrence, whose workgroups stream the batch in
+ * passes of 64 rows and meet at a counter in ws (32-bit word 0) once per time step.  The wait is bounded: if the
+ * workgroups cannot all be resident for that long (another stream occupying the device), the kernel stops early
+ * and sets the 32-bit word 1 of ws to a non-zero value; a kernel enqueued right behind it then overwrites h, s and
+ * gates with NaN, so that such a run cannot pass for a result (a caller may also read word 1 after the stream
+ * has drained).  Where the device cannot hold K/4 such workgroups at once, without `gates` or `ws`, and for other
+ * shapes, every time step is a launch of its own.
  * Two calls that overlap in time must not share `ws`.
  * ------------------------------------------------------------------------ */
 typedef struct {
@@ -281,7 +286,8 @@ int brg_lstm_fwd(const brg_lstm_desc_t *desc, brg_dtype_t dtype, const void *x, 
  * gates and states, and dh_{t-1} += sum_g R_g^T dz_g is one batch-reduce chain of 4 K/bk weight
  * blocks per output block; dx, dW4, dR4 and db4 are sums over all time steps computed afterwards.
  * `ws`: DEVICE memory, 16-byte aligned, at least brg_lstm_bwd_ws_bytes(desc) bytes (the dz of all
- * steps and seventeen [N][K] buffers), contents undefined afterwards; required.  fp32 only.  Correct for every
+ * steps and seventeen [N][K] buffers), contents undefined afterwards; required.  fp32 only (BRG_BF16 returns
+ * BRG_EUNSUPPORTED: the bf16 layer has a forward pass only in this build).  Correct for every
  * shape; with bc = bk = 64 and N a multiple of 64 the GEMMs run on the kernel for 64 x 64 x 64 blocks,
  * otherwise on the general one.
  * ------------------------------------------------------------------------ */

@@ -384,6 +384,27 @@ def lstm_fwd(d: LstmShape, x, W4, R4, b4=None, h0=None, s0=None, want_gates=True
     return h, s, g
 
 
+def lstm_fwd_bf16(d: LstmShape, x, W4, R4, b4=None, h0=None, s0=None):
+    """The LSTM layer with bf16 operands (section 2 of the paper: the kernel is agnostic of the compute precision;
+    the paper gives no recipe for the recurrence, this is the reading the GPU path documents): x, W4, R4 and h0
+    hold bf16-representable values; every step is equations 1-6 in double precision (``lstm_fwd`` with T = 1) on
+    the STORED h_{t-1}; h_t is rounded to bf16 (nearest even) once, when it is stored, and that stored value is what
+    step t+1 multiplies; the cell state and the gate values are kept in fp32.  Returns h (bf16 values), s, gates."""
+    d1 = LstmShape(1, d.N, d.C, d.K, d.bn, d.bc, d.bk)
+    x = _f32(x)
+    h = np.empty((d.T, d.N, d.K), np.float32)
+    s = np.empty((d.T, d.N, d.K), np.float32)
+    g = np.empty((4, d.T, d.N, d.K), np.float32)
+    hp, sp = h0, s0
+    for t in range(d.T):
+        ht, st, gt = lstm_fwd(d1, x[t:t + 1], W4, R4, b4, hp, sp)
+        h[t] = round_bf16(ht[0])
+        s[t] = st[0]
+        g[:, t] = gt[:, 0]
+        hp, sp = h[t], s[t]
+    return h, s, g
+
+
 def lstm_bwd(d: LstmShape, x, W4, R4, h0, s0, h, s, gates, dh, ds_last=None):
     """Reverse-mode derivative of the LSTM layer in float64 (paper section 3.1: equations 1-6 define the
     forward pass; the paper reports the backward / weight-update pass without listing it, so this is the

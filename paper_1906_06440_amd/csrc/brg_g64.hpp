@@ -51,6 +51,10 @@ struct G64Job {
     float *rowsum;
     // G64_COLSUM (stand-alone form of the same sum, used when no GEMM carries it)
     int cs_rows;                 // rows per block (bn)
+    // Ragged last tile column (64-wide tiles, B blocks with the reduction index contiguous only): when non-zero, C
+    // has n_cols columns in all; the rows of B beyond them are not read (the last valid row is read again instead)
+    // and the columns of C beyond them are not written.
+    int n_cols;
 };
 
 constexpr int G64_MAXJOBS = 16;
@@ -153,7 +157,9 @@ template <int TN, bool AKF, bool BKF> __device__ __forceinline__ void g64_tile(c
 #pragma unroll
     for (int j = 0; j < B_ROWS / 16; ++j) {
         const int r = (B_ROWS / 4) * wv + 4 * j + (lane >> 4);
-        gb_off[j] = r * J.b_ld + (((lane & 15) ^ (r & 15)) << 2);
+        int rr = r;
+        if (TN == 64 && J.n_cols && tn * 64 + r >= J.n_cols) rr = J.n_cols - 1 - tn * 64;
+        gb_off[j] = rr * J.b_ld + (((lane & 15) ^ (r & 15)) << 2);
     }
     float4v ra[4], rm[4];   // register path of a masked operand
 #pragma unroll
@@ -359,6 +365,7 @@ template <int TN, bool AKF, bool BKF> __device__ __forceinline__ void g64_tile(c
 #pragma unroll
         for (int y = 0; y < NB; ++y) {
             const int n = wn + (bkf ? 16 * y + li : 2 * li + y);
+            if (TN == 64 && J.n_cols && tn * 64 + n >= J.n_cols) continue;
             const int64_t off = (int64_t)n * J.c_ld + m;
             float4v v = akf ? acc[h][y]
                             : float4v{acc[0][y][2 * h], acc[1][y][2 * h], acc[0][y][2 * h + 1], acc[1][y][2 * h + 1]};

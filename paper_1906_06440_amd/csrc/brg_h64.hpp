@@ -42,6 +42,14 @@ struct H64Args {
     float alpha, beta;
     int64_t a_tile, a_chain, b_tile, b_chain, c_tile_m, c_tile_n;   // element strides
     int a_ld, b_ld, c_ld;                           // row pitch of the staged blocks / of C, in elements
+    // Optional: several stacked problems in one launch.  With m_inner > 0 the row tile tm stands for (tm / m_inner,
+    // tm % m_inner) and the C block starts at (tm / m_inner) * c_outer + (tm % m_inner) * c_tile_m; A and bias are
+    // indexed by tm as a whole (the four gate matrices of an LSTM, stored back to back).
+    int m_inner;
+    int64_t c_outer;
+    // Ragged last tile column (B blocks with the reduction index contiguous only): when non-zero, C has n_cols
+    // columns in all; rows of B beyond them are not read (the last valid row is read again) and not written in C.
+    int n_cols;
 };
 
 typedef float h64_f2v __attribute__((ext_vector_type(2)));
@@ -81,8 +89,10 @@ template <bool AKF, bool BKF, bool PTRS, typename TOut> __global__ __launch_boun
     for (int j = 0; j < 2; ++j) {
         const int r = 16 * wv + 8 * j + (lane >> 3);
         const int piece = (lane & 7) ^ (r & 7);
+        int rb = r;
+        if (BKF && a.n_cols && tn * 64 + r >= a.n_cols) rb = a.n_cols - 1 - tn * 64;
         ga_off[j] = r * a.a_ld + piece * 8;
-        gb_off[j] = r * a.b_ld + piece * 8;
+        gb_off[j] = rb * a.b_ld + piece * 8;
     }
     bool direct = true;
     if (PTRS) {
@@ -224,7 +234,8 @@ template <bool AKF, bool BKF, bool PTRS, typename TOut> __global__ __launch_boun
 
     // ---- epilogue: register r of lane l of tile (x, y) is row m = 16 x + 4 (l / 16) + r, column n = 16 y + l % 16
     // of the wave's piece; a lane owns runs of four consecutive m, the contiguous index of C.
-    TOut *Cb = (TOut *)a.C + tm * a.c_tile_m + tn * a.c_tile_n;
+    TOut *Cb = (TOut *)a.C + tn * a.c_tile_n +
+               (a.m_inner > 0 ? (tm / a.m_inner) * a.c_outer + (tm % a.m_inner) * a.c_tile_m : tm * a.c_tile_m);
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
         const int m = wm + 16 * x + 4 * kg;
@@ -233,6 +244,7 @@ template <bool AKF, bool BKF, bool PTRS, typename TOut> __global__ __launch_boun
 #pragma unroll
         for (int y = 0; y < 2; ++y) {
             const int n = wn + 16 * y + li;
+            if (a.n_cols && tn * 64 + n >= a.n_cols) continue;
             TOut *dst = Cb + (int64_t)n * a.c_ld + m;
             float4v v = acc[x][y] * a.alpha;
             if (a.beta != 0.f) {

@@ -89,8 +89,12 @@ def test_fc_and_lstm_argument_validation(lib):
     assert lib.brg_fc_bwd(C.byref(d16), 1, A16, A16, A16, A16, brg.ACT_RELU, A16, None, None, A16 + 8,
                           None) == brg.EALIGN      # misaligned workspace
     ld = brg.LstmDesc(T=2, N=4, C=64, K=64, bn=4, bc=64, bk=64)
-    assert lib.brg_lstm_fwd(C.byref(ld), 1, A16, A16, A16, None, None, None, A16, A16, None, None,
-                            None) == brg.EUNSUPPORTED
+    assert lib.brg_lstm_fwd(C.byref(ld), 7, A16, A16, A16, None, None, None, A16, A16, None, None,
+                            None) == brg.EINVAL       # bad dtype (fp32 and bf16 are both built)
+    assert lib.brg_lstm_fwd(C.byref(ld), 1, A16 + 2, A16, A16, None, None, None, A16, A16, None, None,
+                            None) == brg.EALIGN
+    assert lib.brg_lstm_fwd(C.byref(ld), 1, A16, A16, A16, None, None, None, A16, A16, A16, A16 + 4,
+                            None) == brg.EALIGN       # misaligned workspace
     assert lib.brg_lstm_fwd(C.byref(brg.LstmDesc(T=2, N=4, C=60, K=64, bn=4, bc=64, bk=64)), 0, A16, A16, A16,
                             None, None, None, A16, A16, None, None, None) == brg.EINVAL
     assert lib.brg_lstm_fwd(C.byref(ld), 0, A16, A16, A16, None, None, None, None, A16, None, None,

@@ -6,7 +6,7 @@ import torch
 import oracle as orc
 import paper_1906_06440_amd as brg
 import workloads as wl
-from gpu_util import check, dev, empty, host, workspace
+from gpu_util import as_seen_by_gpu, check, dev, empty, host, workspace
 
 pytestmark = pytest.mark.gpu
 
@@ -18,13 +18,14 @@ def _bwd_widen(T):
     return max(1.0, float(T) ** 0.5)
 
 
-def gpu_lstm(d, x, W4, R4, b4=None, h0=None, s0=None, want_gates=True, use_ws=True):
+def gpu_lstm(d, x, W4, R4, b4=None, h0=None, s0=None, want_gates=True, use_ws=True, dtype=brg.F32):
+    """dtype BF16: x, W4, R4, h0 and the result h are bf16; bias, cell state and gate values stay fp32."""
     desc = brg.LstmDesc(d.T, d.N, d.C, d.K, d.bn, d.bc, d.bk)
-    h, s = empty((d.T, d.N, d.K)), empty((d.T, d.N, d.K))
+    h, s = empty((d.T, d.N, d.K), dtype), empty((d.T, d.N, d.K))
     g = empty((4, d.T, d.N, d.K)) if want_gates else None
-    opt = lambda a: None if a is None else dev(a)
+    opt = lambda a, dt=brg.F32: None if a is None else dev(a, dt)
     ws = workspace(64) if use_ws else None   # grid-barrier words (cleared by the library)
-    brg.brg_lstm_fwd(desc, brg.F32, dev(x), dev(W4), dev(R4), opt(b4), opt(h0), opt(s0), h, s, g, ws)
+    brg.brg_lstm_fwd(desc, dtype, dev(x, dtype), dev(W4, dtype), dev(R4, dtype), opt(b4), opt(h0, dtype), opt(s0), h, s, g, ws)
     torch.cuda.synchronize()
     if ws is not None:   # word 1 of the workspace: the resident kernel gave up waiting
         assert int(ws[:8].view(torch.int32)[1].item()) == 0, "recurrent kernel reported a barrier time-out"
@@ -140,3 +141,83 @@ def test_lstm_general_path_forced(monkeypatch):
     check(h, rh, brg.F32, "h (general)")
     check(s, rs, brg.F32, "s (general)")
     check(g, rg, brg.F32, "gates (general)")
+
+
+def _check_bf16_lstm(d, x, W4, R4, b4, h0, s0, h, s, g, what):
+    """bf16 layer against the oracle's reading (h_t rounded to bf16 when stored and fed back rounded; fp32 state and
+    gates).  (1) Whole sequence at the stated bf16 tolerance.  (2) Step by step from the GPU's OWN stored h_{t-1},
+    s_{t-1} -- both sides then round the same sums, so every element must agree to the element-wise bound: a
+    one-spacing difference of a stored h_t would otherwise feed every later step."""
+    rh, rs, rg = orc.lstm_fwd_bf16(d, x, W4, R4, b4, h0, s0)
+    assert orc.rel_fro(h, rh) <= 1e-2 and orc.rel_fro(s, rs) <= 1e-2 and orc.rel_fro(g, rg) <= 1e-2, what
+    d1 = orc.LstmShape(1, d.N, d.C, d.K, d.bn, d.bc, d.bk)
+    for t in range(d.T):
+        hp = h[t - 1] if t else h0
+        sp = s[t - 1] if t else s0
+        th, ts, tg = orc.lstm_fwd(d1, x[t:t + 1], W4, R4, b4, hp, sp)
+        check(h[t], orc.round_bf16(th[0]), brg.BF16, "%s h step %d" % (what, t), brg.BF16)
+        check(s[t], ts[0], brg.BF16, "%s s step %d" % (what, t), brg.F32)
+        check(g[:, t], tg[:, 0], brg.BF16, "%s gates step %d" % (what, t), brg.F32)
+
+
+@pytest.mark.parametrize("T,N,C,K,bc,bk", [(3, 16, 64, 64, 64, 64), (4, 20, 96, 80, 32, 16), (5, 64, 128, 192, 64, 64), (1, 3, 8, 8, 8, 8),
+                                           (6, 32, 192, 256, 64, 64), (4, 70, 64, 128, 64, 64), (3, 168, 128, 64, 64, 64),
+                                           (2, 250, 64, 64, 64, 64)])
+def test_lstm_bf16_small(T, N, C, K, bc, bk):
+    """bf16 layer: resident kernel (64-wide blocks; one to four batch passes, ragged T*N) and the general path."""
+    x, W4, R4, b4 = wl.cfg4_lstm(T, N, C, K, bc, bk, with_bias=True, seed_extra=T + N + 1)
+    W4 *= 4.0
+    R4 *= 4.0
+    rng = np.random.default_rng(T * N + 3)
+    h0, s0 = wl.uniform(rng, (N, K), -0.5, 0.5), wl.uniform(rng, (N, K), -0.5, 0.5)
+    x, W4, R4, h0 = (as_seen_by_gpu(v, brg.BF16) for v in (x, W4, R4, h0))
+    d = orc.LstmShape(T, N, C, K, 16, bc, bk)
+    for kw in (dict(b4=b4, h0=h0, s0=s0), dict(b4=None, h0=None, s0=None)):
+        h, s, g = gpu_lstm(d, x, W4, R4, dtype=brg.BF16, **kw)
+        _check_bf16_lstm(d, x, W4, R4, kw["b4"], kw["h0"], kw["s0"], h, s, g, "bf16 lstm")
+    # no workspace: one general launch per time step
+    h, s, g = gpu_lstm(d, x, W4, R4, b4=b4, h0=h0, s0=s0, use_ws=False, dtype=brg.BF16)
+    _check_bf16_lstm(d, x, W4, R4, b4, h0, s0, h, s, g, "bf16 lstm (general path)")
+
+
+@pytest.mark.parametrize("T,N,C,K", [(4, 70, 64, 128), (3, 168, 128, 64), (2, 250, 64, 64), (3, 129, 192, 256)])
+def test_lstm_fp32_more_than_64_batch_rows_on_the_resident_kernel(T, N, C, K):
+    """N > 64: two to four batch passes per step; T*N not a multiple of the projection tile."""
+    x, W4, R4, b4 = wl.cfg4_lstm(T, N, C, K, 64, 64, with_bias=True, seed_extra=T + N + 2)
+    W4 *= 4.0
+    R4 *= 4.0
+    rng = np.random.default_rng(T * N + 5)
+    h0, s0 = wl.uniform(rng, (N, K), -0.5, 0.5), wl.uniform(rng, (N, K), -0.5, 0.5)
+    d = orc.LstmShape(T, N, C, K, 16, 64, 64)
+    h, s, g = gpu_lstm(d, x, W4, R4, b4=b4, h0=h0, s0=s0)
+    rh, rs, rg = orc.lstm_fwd(d, x, W4, R4, b4=b4, h0=h0, s0=s0)
+    check(h, rh, brg.F32, "h")
+    check(s, rs, brg.F32, "s")
+    check(g, rg, brg.F32, "gates")
+
+
+@pytest.mark.parametrize("dtype", [brg.F32, brg.BF16])
+def test_lstm_paper_minibatch_168(dtype):
+    """The minibatch of the paper's LSTM experiment (section 4.1.1: N = 168, C = K = 1024), twelve time steps."""
+    T, N = 12, 168
+    x, W4, R4, _ = wl.cfg4_lstm(T, N)
+    d = orc.LstmShape(T, N, 1024, 1024, 16, 64, 64)
+    if dtype == brg.BF16:
+        x, W4, R4 = (as_seen_by_gpu(v, brg.BF16) for v in (x, W4, R4))
+        h, s, g = gpu_lstm(d, x, W4, R4, dtype=brg.BF16)
+        _check_bf16_lstm(d, x, W4, R4, None, None, None, h, s, g, "N=168 bf16")
+    else:
+        h, s, g = gpu_lstm(d, x, W4, R4)
+        rh, rs, rg = orc.lstm_fwd(d, x, W4, R4)
+        check(h, rh, brg.F32, "h")
+        check(s, rs, brg.F32, "s")
+        check(g, rg, brg.F32, "gates")
+
+
+def test_config4_full_size_bf16():
+    """cfg4's shape (T = 50, N = 64, C = K = 1024) with bf16 operands."""
+    x, W4, R4, _ = wl.cfg4_lstm()
+    x, W4, R4 = (as_seen_by_gpu(v, brg.BF16) for v in (x, W4, R4))
+    d = orc.LstmShape(50, 64, 1024, 1024, 16, 64, 64)
+    h, s, g = gpu_lstm(d, x, W4, R4, dtype=brg.BF16)
+    _check_bf16_lstm(d, x, W4, R4, None, None, None, h, s, g, "cfg4 bf16")

@@ -271,3 +271,40 @@ def test_lstm_bwd_matches_central_differences():
         fd = (loss(plus) - loss(minus)) / (2 * eps)
         an = float((f64(grads[k]) * v).sum())
         assert abs(fd - an) <= 2e-5 * max(1.0, abs(an)), (k, fd, an)
+
+
+def test_lstm_bf16_reading_against_an_explicit_float64_recurrence_with_torch_bf16_rounding():
+    """oracle.lstm_fwd_bf16: h_t rounded to bf16 when stored and fed back rounded; cell state and gates not rounded.
+    Pinned against the equations written out in torch float64 with torch's own bfloat16 cast as the quantiser."""
+    import torch
+    T, N, Cc, K = 5, 3, 16, 8
+    rng = np.random.default_rng(77)
+    d = orc.LstmShape(T, N, Cc, K, 16, 8, 4)
+    q = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).float().numpy()
+    x = q(rng.uniform(-1, 1, (T, N, Cc)))
+    W = q(rng.uniform(-0.6, 0.6, (4, K, Cc)))
+    R = q(rng.uniform(-0.6, 0.6, (4, K, K)))
+    b = rng.uniform(-0.3, 0.3, (4, K)).astype(np.float32)
+    h0 = q(rng.uniform(-0.5, 0.5, (N, K)))
+    s0 = rng.uniform(-0.5, 0.5, (N, K)).astype(np.float32)
+    W4 = np.stack([orc.w2_to_blocked(W[g], d.bc, d.bk) for g in range(4)])
+    R4 = np.stack([orc.w2_to_blocked(R[g], d.bk, d.bk) for g in range(4)])
+    h, s, g = orc.lstm_fwd_bf16(d, x, W4, R4, b, h0, s0)
+    t64 = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    hp, sp = t64(h0), t64(s0)
+    flips = 0
+    for t in range(T):
+        z = [t64(x[t]) @ t64(W[k]).T + hp @ t64(R[k]).T + t64(b[k]) for k in range(4)]
+        i, c, f, o = torch.sigmoid(z[0]), torch.tanh(z[1]), torch.sigmoid(z[2]), torch.sigmoid(z[3])
+        st = f * sp + i * c
+        ht = o * torch.tanh(st)
+        hq = ht.float().to(torch.bfloat16).double()          # stored value: bf16
+        assert np.array_equal(h[t], hq.numpy().astype(np.float32)), "h_t is the bf16 rounding of the step's result"
+        assert np.allclose(s[t], st.numpy(), rtol=1e-6, atol=1e-7) and np.allclose(g[0, t], i.numpy(), rtol=1e-6, atol=1e-7)
+        assert np.allclose(g[3, t], o.numpy(), rtol=1e-6, atol=1e-7) and np.allclose(g[1, t], c.numpy(), rtol=1e-6, atol=1e-7)
+        flips += int((hq != ht).sum())
+        hp, sp = hq, t64(s[t])                              # the rounded h and the fp32-stored state feed the next step
+    assert flips > 0, "the rounding must matter in this test"
+    # feeding the UNROUNDED h forward instead would give different later steps
+    h_plain, _, _ = orc.lstm_fwd(d, x, W4, R4, b, h0, s0)
+    assert not np.array_equal(orc.round_bf16(h_plain[-1]), h[-1])
