@@ -65,8 +65,9 @@ const char *brg_version(void);
  *   BRG_LSTM_GENERAL (flag)   LSTM forward and backward: one general launch per time step
  *   BRG_CONV_GENERAL (flag), BRG_CONV_NO1X1 (flag), BRG_CONV_WGT_GENERAL (flag)
  *                             convolutions: general kernel for all / for 1x1 layers / for the weight gradient
- *   BRG_CONV_KW = 1|2, BRG_CONV_PITCH = 0, BRG_CONV_ZEROFILL (flag), BRG_CONV_NOFUSE (flag)
- *                             tiled bf16 kernel: feature blocks per wave, halo pitch rule, separate zero fill and
+ *   BRG_CONV_KW = 1|2, BRG_CONV_PITCH = 0, BRG_CONV_PLANE_PAD = bytes, BRG_CONV_ZEROFILL (flag), BRG_CONV_NOFUSE (flag)
+ *                             tiled kernels: feature blocks per wave, halo pitch rule, extra bytes between the LDS
+ *                             planes (a multiple of 16; default 0), separate zero fill and
  *                             unfused parity classes of the strided backward pass
  *   BRG_CONV_1X1_KW = 1|2|4, BRG_CONV_1X1_PG = 2|4, BRG_CONV_1X1_WF = 1|2|4, BRG_CONV_1X1_SPLIT = 0|1,
  *   BRG_CONV_1X1_LDS = 0|1, BRG_CONV_1X1_LDS_NGW = 2|4, BRG_CONV_1X1_LDS_PM = 0|1

@@ -14,6 +14,16 @@
 
 namespace brg {
 
+// Distance (modulo 256 bytes) between the LDS planes that the four 16-lane groups of an operand read address.
+// Measured with a read-pattern micro-benchmark and the SQ_LDS_BANK_CONFLICT counter: a 16-byte-per-lane read
+// is served without conflicts when the four groups have the SAME offset modulo 256 bytes (any common shift),
+// and takes twice the LDS cycles when the groups are 16, 64 or 128 bytes apart.
+static int conv_plane_pad()
+{
+    return knobs().conv_plane_pad.set ? knobs().conv_plane_pad.val : 0;
+}
+
+
 struct ConvDims {
     int N, C, H, W, K, R, S, sh, sw, ph, pw, bc, bk, P, Q, Cb, Kb;
 };
@@ -358,7 +368,7 @@ static ConvTilePlan plan_conv_tile(const ConvDims &d, bool bwd, bool bf16 = fals
         pl.KW = a.Kb >= 8 ? 2 : 1;
     }
     int plane = nv_max * a.Wp * 16;
-    plane = ((plane + 255) / 256) * 256 + 64;   // planes start 64 B apart modulo 256
+    plane = ((plane + 255) / 256) * 256 + conv_plane_pad();
     a.plane_bytes = plane;
     a.buf_bytes = pl.CG * cpp * plane;
     pl.smem = 2 * (size_t)a.buf_bytes;
@@ -443,12 +453,12 @@ static Bf16Plan plan_view_bf16(const ConvView &v, int grids = 1)
     a.Hv = (a.P - 1) * v.str + v.R;
     int wp = (a.Q - 1) * v.str + v.S;
     a.Wp = wp > a.W + a.pw ? wp : a.W + a.pw;
-    // A group of output pixels may run over the end of an image row.  With unit stride its operand reads
-    // (16 bytes per pixel, 8 lanes per LDS clock) are free of bank conflicts only if the halo row pitch is
-    // congruent to Q modulo 8 pixels, so that the next row continues where this one ended.  The padding
-    // pays for rows of 8..15 pixels, where EVERY 16-lane group crosses a row end (measured: 8 % on the 14x14
-    // layers; wider rows cross less often and gain nothing, 7x7 tiles lose more to the larger halo than
-    // they gain).
+    // A group of output pixels may run over the end of an image row; its operand read is then free of bank
+    // conflicts only if the next row continues where this one ended.  Full congruence of the halo row pitch with
+    // Q (modulo 16 pixels = 256 bytes, measured with a read-pattern micro-benchmark and SQ_LDS_BANK_CONFLICT) was
+    // tried on every layer and lost: these kernels are not bound by LDS cycles, and the wider halos cost more than
+    // the conflicts (14x14: 22.8 -> 24.9 us, 7x7: 31 -> 38 us).  Kept: congruence modulo 8 pixels for rows of
+    // 8..15 pixels, where EVERY 16-lane group crosses a row end (measured: 8 % on the 14x14 layers).
     if (v.str == 1 && v.R * v.S > 1 && a.Cb > 1 && a.Q >= 8 && a.Q < 16 &&
         !(knobs().conv_pitch.set && knobs().conv_pitch.val == 0))
         a.Wp += ((a.Q - a.Wp) % 8 + 8) % 8;
@@ -489,7 +499,7 @@ static Bf16Plan plan_view_bf16(const ConvView &v, int grids = 1)
         if (v.str != 1 || a.Cb % 2 != 0 || chunks > 1024) return pl;
         NPASS = chunks <= 512 ? 2 : 4;
         // four channel blocks per stage when they fit two workgroups per CU, else two
-        const int plane4 = ((nv_max * a.Wp * 16 + 255) / 256) * 256 + 64;
+        const int plane4 = ((nv_max * a.Wp * 16 + 255) / 256) * 256 + conv_plane_pad();
         CG = (a.Cb % 4 == 0 && 2 * 4 * 2 * plane4 <= 80 * 1024) ? 4 : 2;
         if (CG == 2 && NPASS == 2) NPASS = 4;   // (only the deeper copy plan is instantiated for two blocks)
     }
@@ -500,7 +510,7 @@ static Bf16Plan plan_view_bf16(const ConvView &v, int grids = 1)
     if (pl.KW == 2 && (grids * a.ntiles * ((a.Kb + 7) / 8) < 192 || pl.key == 33228)) pl.KW = 1;
     if (knobs().conv_kw.set) pl.KW = knobs().conv_kw.val == 1 ? 1 : (knobs().conv_kw.val == 2 && a.Kb >= 8 && pl.key != 33228 ? 2 : pl.KW);   // tuning knob
     int plane = nv_max * a.Wp * 16;
-    plane = ((plane + 255) / 256) * 256 + 64;
+    plane = ((plane + 255) / 256) * 256 + conv_plane_pad();
     a.plane_bytes = plane;
     a.buf_bytes = CG * 2 * plane;
     pl.smem = 2 * (size_t)a.buf_bytes;

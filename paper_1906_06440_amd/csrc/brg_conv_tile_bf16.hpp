@@ -66,8 +66,9 @@ __device__ __forceinline__ void conv_tile_bf16_body(const ConvTileArgs &a, int b
     constexpr int TAPS = R * S;
     constexpr int SP = (S + 1) / 2;             // tap pairs per filter row
     constexpr int UNITS = TP ? R * SP : (CG / 2) * TAPS;     // MFMA K-steps per stage
-    // weight ring: depth divides UNITS so that ring slots are compile-time; WD-1 units of prefetch
-    constexpr int WD = UNITS % 3 == 0 ? 3 : (UNITS % 4 == 0 ? 4 : 2);
+    // weight ring: depth divides UNITS so that ring slots are compile-time; WD-1 units of prefetch (five where one
+    // feature block per wave leaves the registers for it: measured 6 % on the 7x7 layers, nothing elsewhere)
+    constexpr int WD = (UNITS % 6 == 0 && KW == 1) ? 6 : (UNITS % 3 == 0 ? 3 : (UNITS % 4 == 0 ? 4 : 2));
     static_assert(UNITS % WD == 0, "ring depth must divide the units of a stage");
 
     const int t = threadIdx.x, lane = t & 63;

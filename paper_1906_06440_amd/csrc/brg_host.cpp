@@ -28,6 +28,7 @@ static void load_knobs()
 #define BRG_KNOB(field, name) read_knob(k.field, name)
     BRG_KNOB(conv_general, "BRG_CONV_GENERAL");
     BRG_KNOB(conv_pitch, "BRG_CONV_PITCH");
+    BRG_KNOB(conv_plane_pad, "BRG_CONV_PLANE_PAD");
     BRG_KNOB(conv_kw, "BRG_CONV_KW");
     BRG_KNOB(conv_no1x1, "BRG_CONV_NO1X1");
     BRG_KNOB(conv_zerofill, "BRG_CONV_ZEROFILL");
