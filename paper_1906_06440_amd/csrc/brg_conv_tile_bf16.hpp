@@ -173,7 +173,38 @@ __device__ __forceinline__ void conv_tile_bf16_body(const ConvTileArgs &a, int b
         }
     };
 
+    // Pixel p = 16 g + li of a tile is (row p / Q, column p % Q) of the tile's run of output rows whatever the
+    // tile: that split is made once (one register per group: invalid flag, row, column).  What changes from tile to
+    // tile is where each ROW lives (image, output row, halo row); threads 0 .. trg-1 work that out once per tile
+    // into a small LDS table, one tile ahead, and every lane then looks its rows up (two index divisions per
+    // lane and group and tile otherwise: more vector instructions than the matrix instructions of a short chain).
+    __shared__ int2 rowtab[2][CT_NG * 16];
+    int pix[CT_NG];
+#pragma unroll
+    for (int g = 0; g < CT_NG; ++g) {
+        const int p = g * 16 + li;
+        const int rr = fdiv(p, a.Q, a.inv_Q), oi = p - rr * a.Q;
+        pix[g] = rr < a.trg ? (rr << 8) | oi : (1 << 20);
+    }
+    auto fill_rowtab = [&](int tile, int tb) {
+        if (t < a.trg) {
+            const int gr0 = tile * a.trg;
+            const int rows = min(a.trg, a.total_rows - gr0);
+            const int n0 = fdiv(gr0, a.P, a.inv_P);
+            const int v_first = n0 * a.Hv + (gr0 - n0 * a.P) * STR;
+            const bool ok = t < rows;
+            const int gr = gr0 + (ok ? t : 0);
+            const int n = fdiv(gr, a.P, a.inv_P), oj = gr - n * a.P;
+            const int lrow = n * a.Hv + oj * STR - v_first;
+            rowtab[tb][t] = int2{lrow * a.Wp * 16, ok ? ((n * a.Kb * a.Hout + oj * a.osub + a.ooh) * a.Wout) * 16 : -1};
+        }
+    };
+    const int pcol0 = TP ? (kg & 1) * a.plane_bytes + (kg >> 1) * 16 : kg * a.plane_bytes;
+    const int pout0 = (kb0 * a.Hout * a.Wout + a.oow) * 16 + 4 * kg;
+    int tb = 0;
+
     plan(xcd_tile(tile_v, a.ntiles));
+    fill_rowtab(xcd_tile(tile_v, a.ntiles), 0);
     load_halo(0);
 #pragma unroll
     for (int d = 0; d < WD - 1; ++d) load_w(0, d, wring[d]);
@@ -187,25 +218,13 @@ __device__ __forceinline__ void conv_tile_bf16_body(const ConvTileArgs &a, int b
         const bool has_next = next_v < a.ntiles;
 
         int bbase[CT_NG], ooff[CT_NG];
-        {
-            const int gr0 = tile * a.trg;
-            const int rows = min(a.trg, a.total_rows - gr0);
-            const int n0 = fdiv(gr0, a.P, a.inv_P);
-            const int v_first = n0 * a.Hv + (gr0 - n0 * a.P) * STR;
 #pragma unroll
-            for (int g = 0; g < CT_NG; ++g) {
-                const int p = g * 16 + li;
-                const int rr = fdiv(p, a.Q, a.inv_Q), oi = p - rr * a.Q;
-                const bool ok = rr < rows;
-                const int gr = gr0 + (ok ? rr : 0);
-                const int n = fdiv(gr, a.P, a.inv_P), oj = gr - n * a.P;
-                const int lrow = n * a.Hv + oj * STR - v_first;
-                // plane of this lane inside a channel-block pair: (kg >> 1) * 2 + (kg & 1) = kg
-                bbase[g] = TP ? (kg & 1) * a.plane_bytes + (lrow * a.Wp + (ok ? oi : 0) * STR + (kg >> 1)) * 16
-                              : kg * a.plane_bytes + (lrow * a.Wp + (ok ? oi : 0) * STR) * 16;
-                ooff[g] = ok ? (((n * a.Kb + kb0) * a.Hout + oj * a.osub + a.ooh) * a.Wout + oi * a.osub + a.oow) * 16 + 4 * kg
-                             : -1;
-            }
+        for (int g = 0; g < CT_NG; ++g) {
+            const bool dead = pix[g] >> 20;
+            const int2 e = rowtab[tb][(pix[g] >> 8) & 255];          // (row 0 for lanes beyond the tile: in bounds)
+            const int oi = pix[g] & 255;
+            bbase[g] = pcol0 + e.x + oi * (STR * 16);
+            ooff[g] = (dead || e.y < 0) ? -1 : e.y + pout0 + oi * a.osub * 16;
         }
 
         float4v acc[KW][CT_NG];
@@ -217,7 +236,10 @@ __device__ __forceinline__ void conv_tile_bf16_body(const ConvTileArgs &a, int b
         for (int sidx = 0; sidx < nstage; ++sidx) {
             const bool last = sidx + 1 == nstage;
             const bool more = !last || has_next;
-            if (last && has_next) plan(xcd_tile(next_v, a.ntiles));
+            if (last && has_next) {
+                plan(xcd_tile(next_v, a.ntiles));
+                fill_rowtab(xcd_tile(next_v, a.ntiles), tb ^ 1);
+            }
             if (more) load_halo(last ? 0 : sidx + 1);
 
             const unsigned char *sbuf = smem + buf * a.buf_bytes;
@@ -305,6 +327,7 @@ __device__ __forceinline__ void conv_tile_bf16_body(const ConvTileArgs &a, int b
         act_dispatch(a.act, epilogue);
         if (!has_next) break;
         tile_v = next_v;
+        tb ^= 1;
     }
 }
 

@@ -40,6 +40,7 @@ static void load_knobs()
     BRG_KNOB(conv_1x1_lds_pm, "BRG_CONV_1X1_LDS_PM");
     BRG_KNOB(conv_1x1_split, "BRG_CONV_1X1_SPLIT");
     BRG_KNOB(conv_1x1_wf, "BRG_CONV_1X1_WF");
+    BRG_KNOB(conv_1x1_ring, "BRG_CONV_1X1_RING");
     BRG_KNOB(conv_stem_classes, "BRG_CONV_STEM_CLASSES");
     BRG_KNOB(conv_stem_gx, "BRG_CONV_STEM_GX");
     BRG_KNOB(conv_wgt_general, "BRG_CONV_WGT_GENERAL");
