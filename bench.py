@@ -556,6 +556,10 @@ def main():
         r5 = run_cfg5(10, 3, with_upd=True)
         others["cfg5"] = dict({"workload": "53 conv layers of ResNet-50 v1.5, N=64, bf16 in/out, weighted (bwd_wgt: fp32 result); "
                                            "per layer: warm = one buffer set, cold = rotating buffer sets > 512 MB"}, **r5)
+        r1 = run_cfg5(10, 3, N=1, cold=False)   # the inference shapes of section 4.3: one image
+        others["cfg5_n1"] = {"workload": "53 conv layers of ResNet-50 v1.5, N=1, bf16 in/out, weighted, forward (inference)",
+                             "weighted_tflops": r1["fwd"]["weighted_tflops"], "total_ms_53_layers": r1["fwd"]["total_ms_53_layers"],
+                             "us_per_layer": {row["layer"]: row["us"] for row in r1["fwd"]["layers"]}}
         line["others"] = others
     if not args.no_cpu_baseline and args.workload == "cfg2":
         line["cpu_baseline"] = cpu_baseline_cfg2()

@@ -10,6 +10,7 @@
 #include "brg_conv1x1_bf16.hpp"
 #include "brg_conv1x1_lds_bf16.hpp"
 #include "brg_conv1x1_ring_bf16.hpp"
+#include "brg_conv_small_bf16.hpp"
 #include "brg_conv_stem_bf16.hpp"
 #include "brg_conv_wgt.hpp"
 
@@ -714,6 +715,106 @@ static int conv1x1_bf16_launch(const ConvView &v, const void *I, const void *Wt,
     return conv1x1_go<1, 2>(a, grid, wtr, s);
 }
 
+// ---- few output pixels (a small minibatch): feature blocks first, and the chain divided too
+struct ConvSmallPlan {
+    bool ok;
+    int KW, PG, gz, upp;
+    int64_t ws_bytes;   // fp32 partial results when gz > 1
+};
+
+// `can_split`: a workspace may carry partial results (forward pass).  Chosen when tiling pixels x feature blocks
+// alone cannot give every CU a workgroup, or when BRG_CONV_SMALL=1 asks for it on any shape the kernel covers.
+static ConvSmallPlan conv_small_plan(const ConvView &v, bool can_split)
+{
+    ConvSmallPlan pl = {};
+    const int taps = v.R * v.S;
+    const int64_t npix = (int64_t)v.N * v.P * v.Q;
+    if (v.R > 4 || v.S > 4 || taps > 16 || (v.Cb & 1) || v.P <= 0 || v.Q <= 0 || v.str < 1 || v.str > 2 || v.ph < 0 || v.pw < 0) return pl;
+    // (the input below 2 GiB: the kernel's out-of-range offset must lie beyond it)
+    if (npix * v.Kb >= (1 << 22) || (int64_t)v.N * v.Cb * v.Hin * v.Win * 32 >= (1ll << 31) ||
+        (int64_t)v.N * v.Kb * v.Hout * v.Wout * 16 >= (1ll << 31))
+        return pl;
+    if ((v.P - 1) * v.osub + v.ooh >= v.Hout || (v.Q - 1) * v.osub + v.oow >= v.Wout) return pl;
+    if ((v.H - 1) * v.sub >= v.Hin || (v.W - 1) * v.sub >= v.Win) return pl;
+    const int dr = v.R > 1 ? v.wtap[v.S] - v.wtap[0] : 0, ds = v.S > 1 ? v.wtap[1] - v.wtap[0] : 0;
+    for (int t = 0; t < taps; ++t)   // the kernel steps through the taps with one stride per direction
+        if (v.wtap[t] != v.wtap[0] + (t / v.S) * dr + (t % v.S) * ds) return pl;
+    if (knobs().conv_small.set && knobs().conv_small.val == 0) return pl;
+    const int units = (v.Cb >> 1) * taps;
+    if (units >= 4096) return pl;   // (the kernel's multiply-and-shift divisions)
+    const int groups = (int)((npix + 15) / 16);
+    // operand reuse per wave as long as the grid still covers the device
+    int KW = v.Kb >= 2 ? 2 : 1, PG = groups >= 2 ? 2 : 1;
+    auto wgs = [&](int kw, int pg) { return (int64_t)((groups + pg - 1) / pg) * ((v.Kb + kw - 1) / kw); };
+    if (wgs(KW, PG) < 256) PG = 1;
+    if (wgs(KW, PG) < 256) KW = 1;
+    const bool forced = knobs().conv_small.on();
+    // with enough pixels for the tiled kernels this kernel (no operand sharing between workgroups) loses
+    if (!forced && wgs(2, 2) > 512) return pl;
+    if (knobs().conv_small_kw.set) { int x = knobs().conv_small_kw.val; if (x == 1 || x == 2) KW = x; }   // tuning knobs
+    if (knobs().conv_small_pg.set) { int x = knobs().conv_small_pg.val; if (x == 1 || x == 2) PG = x; }
+    // Ranges of the chain.  The second pass costs about as much as 16 chain units of a wave, so only long chains
+    // are divided (at most 40 units per wave), or chains of a grid that leaves most CUs without a workgroup.
+    int gz = 1;
+    if (can_split) {
+        gz = (units + 159) / 160;
+        const int64_t w = wgs(KW, PG);
+        if (w < 64) {
+            int fill = (int)(128 / w);
+            if (fill > units / 16) fill = units / 16;
+            if (fill > gz) gz = fill;
+        }
+        if (gz > 16) gz = 16;
+        if (gz < 1) gz = 1;
+        if (knobs().conv_small_gz.set) { int x = knobs().conv_small_gz.val; if (x >= 1 && x <= 16 && x <= units) gz = x; }
+    }
+    pl.upp = (units + gz - 1) / gz;
+    gz = (units + pl.upp - 1) / pl.upp;   // (no empty range)
+    pl.KW = KW; pl.PG = PG; pl.gz = gz;
+    pl.ws_bytes = gz > 1 ? (int64_t)gz * v.Kb * npix * 64 : 0;
+    pl.ok = true;
+    return pl;
+}
+
+template <int KW, int PG> static void conv_small_go(const ConvSmallArgs &a, dim3 grid, bool wtr, hipStream_t s)
+{
+    if (wtr) hipLaunchKernelGGL((conv_small_bf16<KW, PG, true>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((conv_small_bf16<KW, PG, false>), grid, dim3(256), 0, s, a);
+}
+
+static int conv_small_launch(const ConvView &v, const ConvSmallPlan &pl, const void *I, const void *Wt, void *O,
+                             const float *bias, int act, bool wtr, void *ws, hipStream_t s)
+{
+    const int64_t npix = (int64_t)v.N * v.P * v.Q;
+    const int taps = v.R * v.S;
+    ConvSmallArgs a = {};
+    a.I = I; a.Wt = Wt; a.O = O; a.part = (float *)ws; a.bias = bias; a.act = act;
+    a.N = v.N; a.Cb = v.Cb; a.Kb = v.Kb; a.P = v.P; a.Q = v.Q;
+    a.Hin = v.Hin; a.Win = v.Win; a.sub = v.sub; a.H = v.H; a.W = v.W;
+    a.str = v.str; a.ph = v.ph; a.pw = v.pw; a.R = v.R; a.S = v.S;
+    a.Hout = v.Hout; a.Wout = v.Wout; a.osub = v.osub; a.ooh = v.ooh; a.oow = v.oow;
+    a.w_ob = v.w_ob; a.w_ib = v.w_ib; a.w_t0 = v.wtap[0]; a.w_dr = v.R > 1 ? v.wtap[v.S] - v.wtap[0] : 0; a.w_ds = v.S > 1 ? v.wtap[1] - v.wtap[0] : 0;
+    a.npix = (int)npix; a.units = (v.Cb >> 1) * taps; a.upp = pl.upp; a.gz = pl.gz;
+    a.inv_PQ = 1.0f / (float)(v.P * v.Q); a.inv_Q = 1.0f / (float)v.Q;
+    a.mdiv_taps = (65536 + taps - 1) / taps; a.mdiv_S = (65536 + v.S - 1) / v.S;
+    a.in_bytes = (int)((int64_t)v.N * v.Cb * v.Hin * v.Win * 32);
+    if (pl.gz > 1) {
+        BRG_REQUIRE(ws != nullptr, BRG_EINVAL, "brg_conv (few pixels): internal: a divided chain without a workspace");
+        BRG_REQUIRE(aligned16(ws), BRG_EALIGN, "brg_conv_fwd: workspace not 16-byte aligned");
+    }
+    const int groups = (int)((npix + 15) / 16);
+    dim3 grid((unsigned)((groups + pl.PG - 1) / pl.PG), (unsigned)((v.Kb + pl.KW - 1) / pl.KW), (unsigned)pl.gz);
+    if (pl.KW == 2 && pl.PG == 2) conv_small_go<2, 2>(a, grid, wtr, s);
+    else if (pl.KW == 2) conv_small_go<2, 1>(a, grid, wtr, s);
+    else if (pl.PG == 2) conv_small_go<1, 2>(a, grid, wtr, s);
+    else conv_small_go<1, 1>(a, grid, wtr, s);
+    int rc = check_launch("brg_conv (few pixels) launch");
+    if (rc || pl.gz == 1) return rc;
+    const int64_t nthr = npix * v.Kb * 4;
+    hipLaunchKernelGGL(conv_small_reduce, dim3((unsigned)((nthr + 255) / 256)), dim3(256), 0, s, a);
+    return check_launch("brg_conv (few pixels, sum of the ranges) launch");
+}
+
 // ---- the 7x7 stride-2 pad-3 stem with one channel block of 4 (bf16 in and out)
 static bool conv_is_stem4(const ConvDims &d)
 {
@@ -924,6 +1025,11 @@ extern "C" int brg_conv_fwd(const brg_conv_desc_t *desc, brg_dtype_t dtype, brg_
         Bf16Plan pl;
         pl.ok = false;
         const bool have_view = conv_fwd_view(d, &v);
+        if (have_view && !knobs().conv_general.set) {
+            // (a workspace sized by brg_conv_ws_bytes holds the partial results of the plan made here)
+            const ConvSmallPlan sp = conv_small_plan(v, ws != nullptr);
+            if (sp.ok) return conv_small_launch(v, sp, I, Wt, O, bias, act, true, ws, s);
+        }
         const bool is1x1 = have_view && conv1x1_bf16_covers(v);
         if (have_view && !is1x1) pl = plan_view_bf16(v);
         if (is1x1 && !knobs().conv_general.set) return conv1x1_bf16_launch(v, I, Wt, O, bias, act, true, ws, s);
@@ -972,6 +1078,7 @@ extern "C" int brg_conv_bwd_data(const brg_conv_desc_t *desc, brg_dtype_t dtype,
         // one tiled pass per stride x stride parity class of the input pixels
         if (d.sh == d.sw && d.sh <= 2 && !knobs().conv_general.set) {
             Bf16Plan plans[4];
+            ConvSmallPlan smalls[4];
             ConvView views[4];
             int np = 0, nclass = d.sh * d.sw;
             bool all_ok = true, holes = false;
@@ -984,7 +1091,8 @@ extern "C" int brg_conv_bwd_data(const brg_conv_desc_t *desc, brg_dtype_t dtype,
                     }
                     if (v.R == 99) { all_ok = false; break; }
                     views[np] = v;
-                    if (conv1x1_bf16_covers(v)) {
+                    smalls[np] = conv_small_plan(v, false);
+                    if (smalls[np].ok || conv1x1_bf16_covers(v)) {
                         plans[np].ok = false;
                     } else {
                         // (the 1x2, 2x1 and 2x2-tap classes of a strided 3x3 layer run as one grid)
@@ -996,7 +1104,7 @@ extern "C" int brg_conv_bwd_data(const brg_conv_desc_t *desc, brg_dtype_t dtype,
             (void)nclass;
             if (all_ok && np > 0) {
                 // 1x1 with stride 2: only class (0, 0) has a tap; its kernel writes the zero pixels itself
-                const bool zsib = holes && np == 1 && d.sh == 2 && conv1x1_bf16_covers(views[0]) && views[0].osub == 2 &&
+                const bool zsib = holes && np == 1 && d.sh == 2 && !smalls[0].ok && conv1x1_bf16_covers(views[0]) && views[0].osub == 2 &&
                                   views[0].ooh == 0 && views[0].oow == 0 && !knobs().conv_zerofill.set;
                 if (zsib) return conv1x1_bf16_launch(views[0], dO, Wt, dI, nullptr, BRG_ACT_NONE, false, nullptr, s, true);
                 if (holes) {
@@ -1043,8 +1151,10 @@ extern "C" int brg_conv_bwd_data(const brg_conv_desc_t *desc, brg_dtype_t dtype,
                 }
                 for (int i = 0; i < np; ++i) {
                     if (fuse && (i == fused[0] || i == fused[1] || i == fused[2])) continue;
-                    rc = conv1x1_bf16_covers(views[i]) ? conv1x1_bf16_launch(views[i], dO, Wt, dI, nullptr, BRG_ACT_NONE, false, nullptr, s)
-                                                       : conv_tile_bf16_launch(plans[i], dO, Wt, dI, nullptr, BRG_ACT_NONE, s);
+                    if (smalls[i].ok) rc = conv_small_launch(views[i], smalls[i], dO, Wt, dI, nullptr, BRG_ACT_NONE, false, nullptr, s);
+                    else
+                        rc = conv1x1_bf16_covers(views[i]) ? conv1x1_bf16_launch(views[i], dO, Wt, dI, nullptr, BRG_ACT_NONE, false, nullptr, s)
+                                                           : conv_tile_bf16_launch(plans[i], dO, Wt, dI, nullptr, BRG_ACT_NONE, s);
                     if (rc) return rc;
                 }
                 return BRG_OK;
@@ -1144,5 +1254,23 @@ extern "C" int64_t brg_conv_ws_bytes(const brg_conv_desc_t *desc, brg_dtype_t dt
     if (dtype != BRG_BF16) return 0;
     const int64_t copy = desc->C * desc->K * desc->R * desc->S * 2;   // a transposed copy of the bf16 weights
     const int64_t rows = desc->K * desc->R * 64;                        // or filter rows padded to 32 elements
-    return desc->bc == 4 ? (rows > copy ? rows : copy) : copy;
+    if (desc->bc == 4) return rows > copy ? rows : copy;
+    // or the partial results of a divided chain (few output pixels)
+    if (desc->N > 0 && desc->H > 0 && desc->W > 0 && desc->stride_h > 0 && desc->stride_w > 0 && desc->pad_h >= 0 && desc->pad_w >= 0 &&
+        desc->bc == 16 && desc->bk == 16 && desc->C % 16 == 0 && desc->K % 16 == 0 && desc->N < (1 << 20) && desc->C < (1 << 20) &&
+        desc->K < (1 << 20) && desc->H < (1 << 15) && desc->W < (1 << 15) && desc->R < 64 && desc->S < 64 &&
+        desc->H + 2 * desc->pad_h >= desc->R && desc->W + 2 * desc->pad_w >= desc->S) {
+        brg::ConvDims d;
+        d.N = (int)desc->N; d.C = (int)desc->C; d.H = (int)desc->H; d.W = (int)desc->W; d.K = (int)desc->K;
+        d.R = (int)desc->R; d.S = (int)desc->S; d.sh = (int)desc->stride_h; d.sw = (int)desc->stride_w;
+        d.ph = (int)desc->pad_h; d.pw = (int)desc->pad_w; d.bc = 16; d.bk = 16;
+        d.P = (d.H + 2 * d.ph - d.R) / d.sh + 1; d.Q = (d.W + 2 * d.pw - d.S) / d.sw + 1;
+        d.Cb = d.C / 16; d.Kb = d.K / 16;
+        brg::ConvView v;
+        if (brg::conv_fwd_view(d, &v)) {
+            const brg::ConvSmallPlan sp = brg::conv_small_plan(v, true);
+            if (sp.ok && sp.ws_bytes > copy) return sp.ws_bytes;
+        }
+    }
+    return copy;
 }

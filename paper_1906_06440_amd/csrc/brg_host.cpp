@@ -41,6 +41,10 @@ static void load_knobs()
     BRG_KNOB(conv_1x1_split, "BRG_CONV_1X1_SPLIT");
     BRG_KNOB(conv_1x1_wf, "BRG_CONV_1X1_WF");
     BRG_KNOB(conv_1x1_ring, "BRG_CONV_1X1_RING");
+    BRG_KNOB(conv_small, "BRG_CONV_SMALL");
+    BRG_KNOB(conv_small_kw, "BRG_CONV_SMALL_KW");
+    BRG_KNOB(conv_small_pg, "BRG_CONV_SMALL_PG");
+    BRG_KNOB(conv_small_gz, "BRG_CONV_SMALL_GZ");
     BRG_KNOB(conv_stem_classes, "BRG_CONV_STEM_CLASSES");
     BRG_KNOB(conv_stem_gx, "BRG_CONV_STEM_GX");
     BRG_KNOB(conv_wgt_general, "BRG_CONV_WGT_GENERAL");

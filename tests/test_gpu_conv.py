@@ -67,8 +67,11 @@ BF16_TILED = [(3, 64, 14, 64, 3, 1, 1), (2, 128, 9, 192, 3, 1, 1), (3, 64, 10, 1
               (3, 128, 13, 64, 1, 2, 0)]
 
 
+@pytest.mark.parametrize("small", ["0", "1"])   # "1": the same shapes on the few-pixel kernel (divided chain with the workspace)
 @pytest.mark.parametrize("N,C,H,K,R,stride,pad", BF16_TILED)
-def test_conv_bf16_tiled_fwd_bwd(N, C, H, K, R, stride, pad):
+def test_conv_bf16_tiled_fwd_bwd(monkeypatch, N, C, H, K, R, stride, pad, small):
+    monkeypatch.setenv("BRG_CONV_SMALL", small)
+    brg.brg_tuning_reload()
     I, W, dO = wl.conv_tensors(N, C, H, K, R, stride, pad, cfg_index=5, seed_extra=C + K, want_dO=True)
     d = orc.ConvShape(N, C, H, H, K, R, R, stride, pad)
     Is, Ws, dOs = (as_seen_by_gpu(v, brg.BF16) for v in (I, W, dO))
@@ -87,12 +90,16 @@ ACTS = [(brg.ACT_NONE, orc.ACT_NONE), (brg.ACT_RELU, orc.ACT_RELU), (brg.ACT_SIG
 
 
 @pytest.mark.parametrize("gact,oact", ACTS)
-@pytest.mark.parametrize("family", ["f32_3x3", "bf16_3x3", "bf16_1x1", "bf16_1x1_split", "bf16_1x1_tiled", "bf16_stem4"])
+@pytest.mark.parametrize("family", ["f32_3x3", "bf16_3x3", "bf16_1x1", "bf16_1x1_split", "bf16_1x1_tiled", "bf16_stem4", "bf16_small",
+                                    "bf16_small_gz1"])
 def test_conv_epilogue_activations(monkeypatch, family, gact, oact):
     bc = 16
+    monkeypatch.setenv("BRG_CONV_SMALL", "1" if family.startswith("bf16_small") else "0")
+    if family == "bf16_small_gz1":
+        monkeypatch.setenv("BRG_CONV_SMALL_GZ", "1")
     if family == "f32_3x3":
         N, C, H, K, R, stride, pad, dt = 2, 32, 9, 48, 3, 1, 1, brg.F32
-    elif family == "bf16_3x3":
+    elif family in ("bf16_3x3", "bf16_small", "bf16_small_gz1"):
         N, C, H, K, R, stride, pad, dt = 2, 64, 10, 80, 3, 1, 1, brg.BF16
     elif family == "bf16_stem4":
         N, C, H, K, R, stride, pad, dt, bc = 2, 3, 26, 64, 7, 2, 3, brg.BF16, 4
@@ -124,6 +131,7 @@ ONE_BY_ONE = [(2, 32, 7, 16, 1), (3, 64, 14, 272, 1), (1, 256, 5, 80, 1), (2, 96
 @pytest.mark.parametrize("N,C,H,K,stride", ONE_BY_ONE + [(2, 512, 7, 64, 1), (1, 544, 5, 32, 1), (2, 256, 14, 272, 1),
                                                          (3, 160, 9, 256, 2), (5, 320, 14, 400, 1), (3, 1024, 7, 144, 1), (4, 256, 13, 128, 2)])
 def test_conv1x1_bf16_streaming(monkeypatch, N, C, H, K, stride, KW, PG):
+    monkeypatch.setenv("BRG_CONV_SMALL", "0")
     if KW > 0:
         monkeypatch.setenv("BRG_CONV_1X1_KW", str(KW))
         monkeypatch.setenv("BRG_CONV_1X1_PG", str(PG))
@@ -143,6 +151,32 @@ def test_conv1x1_bf16_streaming(monkeypatch, N, C, H, K, stride, KW, PG):
     check(gpu_fwd(d, I, W, brg.BF16, brg.BF16, bias=bias, act=brg.ACT_RELU),
           orc.conv_fwd(d, Is, Ws, bias, orc.ACT_RELU, out_bf16=True), brg.BF16, "1x1 fwd")
     check(gpu_bwd_data(d, dO, W, brg.BF16, brg.BF16), orc.conv_bwd_data(d, dOs, Ws, out_bf16=True), brg.BF16, "1x1 bwd")
+
+
+# The few-pixel kernel (feature blocks first, chain divided between the waves of a workgroup and between
+# workgroups): every (feature blocks, pixel groups) variant with 1 .. 16 ranges of the chain, on 3x3 with
+# padding, stride 2, 1x1 with input sub-sampling, 2 .. 128 channel blocks, ragged pixel and feature counts,
+# forward (partial results in the workspace) and backward by data (one range).
+@pytest.mark.parametrize("KW,PG,GZ", [(0, 0, 0), (2, 2, 1), (1, 1, 4), (2, 1, 3), (1, 2, 16), (2, 2, 5)])
+@pytest.mark.parametrize("N,C,H,K,R,stride,pad", [
+    (1, 64, 14, 64, 3, 1, 1), (1, 512, 7, 512, 3, 1, 1), (1, 256, 14, 256, 3, 2, 1), (1, 2048, 7, 512, 1, 1, 0),
+    (2, 96, 9, 48, 1, 2, 0), (3, 32, 5, 16, 3, 1, 1), (1, 64, 28, 80, 3, 1, 1), (1, 128, 13, 48, 3, 2, 1),
+    (1, 32, 6, 272, 2, 1, 0), (2, 64, 7, 32, 4, 1, 2)])
+def test_conv_small_bf16_variants(monkeypatch, N, C, H, K, R, stride, pad, KW, PG, GZ):
+    monkeypatch.setenv("BRG_CONV_SMALL", "1")
+    if KW:
+        monkeypatch.setenv("BRG_CONV_SMALL_KW", str(KW))
+        monkeypatch.setenv("BRG_CONV_SMALL_PG", str(PG))
+        monkeypatch.setenv("BRG_CONV_SMALL_GZ", str(GZ))
+    brg.brg_tuning_reload()
+    I, W, dO = wl.conv_tensors(N, C, H, K, R, stride, pad, cfg_index=5, seed_extra=C + K + H + R, want_dO=True)
+    d = orc.ConvShape(N, C, H, H, K, R, R, stride, pad)
+    Is, Ws, dOs = (as_seen_by_gpu(v, brg.BF16) for v in (I, W, dO))
+    bias = wl.uniform(np.random.default_rng(K), (K,))
+    check(gpu_fwd(d, I, W, brg.BF16, brg.BF16, bias=bias, act=brg.ACT_RELU),
+          orc.conv_fwd(d, Is, Ws, bias, orc.ACT_RELU, out_bf16=True), brg.BF16, "few-pixel fwd")
+    check(gpu_fwd(d, I, W, brg.BF16, brg.BF16, use_ws=False), orc.conv_fwd(d, Is, Ws, out_bf16=True), brg.BF16, "few-pixel fwd, no workspace")
+    check(gpu_bwd_data(d, dO, W, brg.BF16, brg.BF16), orc.conv_bwd_data(d, dOs, Ws, out_bf16=True), brg.BF16, "few-pixel bwd")
 
 
 def test_conv_bf16_stem_tiled():
