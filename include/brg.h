@@ -70,9 +70,12 @@ const char *brg_version(void);
  *                             planes (a multiple of 16; default 0), separate zero fill and
  *                             unfused parity classes of the strided backward pass
  *   BRG_CONV_1X1_KW = 1|2|4, BRG_CONV_1X1_PG = 2|4, BRG_CONV_1X1_WF = 1|2|4, BRG_CONV_1X1_SPLIT = 0|1,
- *   BRG_CONV_1X1_LDS = 0|1, BRG_CONV_1X1_LDS_NGW = 2|4, BRG_CONV_1X1_LDS_PM = 0|1
+ *   BRG_CONV_1X1_LDS = 0|1, BRG_CONV_1X1_LDS_NGW = 2|4, BRG_CONV_1X1_LDS_PM = 0|1, BRG_CONV_1X1_RING = 0|1
  *                             bf16 1x1 layers: wave tile of the streaming kernel, split-reduction and
- *                             workgroup-tiled variants
+ *                             workgroup-tiled variants, the persistent ring-staged variant (off by default)
+ *   BRG_CONV_SMALL = 0|1, BRG_CONV_SMALL_KW = 1|2, BRG_CONV_SMALL_PG = 1|2, BRG_CONV_SMALL_GZ = 1..16
+ *                             bf16 layers on few output pixels: never / wherever the kernel applies; feature blocks
+ *                             and pixel groups per workgroup; ranges of the reduction chain
  *   BRG_CONV_STEM_CLASSES (flag), BRG_CONV_STEM_GX = n
  *                             bf16 7x7 layer on a channel block of 4: per-class backward launches, grid size
  *   BRG_CONV_WGT_PS = 1|2, BRG_CONV_WGT_TARGET = n
@@ -147,8 +150,10 @@ int brg_gemm_strided(brg_dtype_t dtype, brg_dtype_t out_dtype, int64_t m, int64_
  * ws == NULL fp32 reads the weights as stored (a few percent slower); bf16 1x1 layers re-block the
  * weights inside the kernel and need no workspace (only the variant for C >= 1024 on at most
  * 16384 pixels is not chosen without one), other bf16 filters take a slower general kernel (the
- * bc = 4 layer: the same kernel with a slower start).  brg_conv_bwd_data ignores `ws`; for
- * brg_conv_bwd_wgt see brg_conv_bwd_wgt_ws_bytes.
+ * bc = 4 layer: the same kernel with a slower start).  bf16 layers with few output pixels (a small
+ * minibatch, paper section 4.3) run on a kernel that divides the (c-block, r, s) chain between
+ * workgroups; it keeps the fp32 partial results of a long chain in `ws` and, without one, leaves the
+ * chain in one piece.  brg_conv_bwd_data ignores `ws`; for brg_conv_bwd_wgt see brg_conv_bwd_wgt_ws_bytes.
  * ------------------------------------------------------------------------ */
 typedef struct {
     int64_t N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, bc, bk;
