@@ -70,9 +70,9 @@ const char *brg_version(void);
  *                             planes (a multiple of 16; default 0), separate zero fill and
  *                             unfused parity classes of the strided backward pass
  *   BRG_CONV_1X1_KW = 1|2|4, BRG_CONV_1X1_PG = 2|4, BRG_CONV_1X1_WF = 1|2|4, BRG_CONV_1X1_SPLIT = 0|1,
- *   BRG_CONV_1X1_LDS = 0|1, BRG_CONV_1X1_LDS_NGW = 2|4, BRG_CONV_1X1_LDS_PM = 0|1, BRG_CONV_1X1_RING = 0|1
+ *   BRG_CONV_1X1_LDS = 0|1, BRG_CONV_1X1_LDS_NGW = 2|4, BRG_CONV_1X1_LDS_PM = 0|1
  *                             bf16 1x1 layers: wave tile of the streaming kernel, split-reduction and
- *                             workgroup-tiled variants, the persistent ring-staged variant (off by default)
+ *                             workgroup-tiled variants
  *   BRG_CONV_SMALL = 0|1, BRG_CONV_SMALL_KW = 1|2, BRG_CONV_SMALL_PG = 1|2, BRG_CONV_SMALL_GZ = 1..16
  *                             bf16 layers on few output pixels: never / wherever the kernel applies; feature blocks
  *                             and pixel groups per workgroup; ranges of the reduction chain

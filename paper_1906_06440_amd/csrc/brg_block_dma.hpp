@@ -1,8 +1,7 @@
 // Batch-reduce GEMM over 64 x 64 x 64 fp32 blocks, variant with direct global->LDS loads.
 //
-// Same decomposition as block_tile_f32 (one workgroup of 8 waves per 64 x 64 block of C, the
-// chain split between two wave groups, a 32 x 32 piece of C per wave in four MFMA accumulators),
-// but the block pairs never pass through registers: every wave issues `global_load_lds_dwordx4`
+// One workgroup of 8 waves per 64 x 64 block of C, the chain split between two wave groups, a
+// 32 x 32 piece of C per wave in four MFMA accumulators.  The block pairs never pass through registers: every wave issues `global_load_lds_dwordx4`
 // for its share of the next A_i / B_i pair while the current pair is multiplied.  Lane L of such
 // an instruction deposits its 16 bytes at LDS base + 16*L, so a wave instruction fills four rows
 // of 64 floats; bank conflicts are avoided by an XOR swizzle instead of row padding: the 16-byte
@@ -184,7 +183,7 @@ __global__ __launch_bounds__(512, 1) void block_dma_f32(BlockTileArgs a)
         __syncthreads();                                    // ... and so has everybody else's
     }
 
-    // ---- combine the two half-chain partial tiles, epilogue, single store (as in block_tile_f32)
+    // ---- combine the two half-chain partial tiles, epilogue, single store
     float *xch = bd_smem;
     if (grp == 1) {
 #pragma unroll

@@ -9,7 +9,6 @@
 #include "brg_conv_tile_bf16.hpp"
 #include "brg_conv1x1_bf16.hpp"
 #include "brg_conv1x1_lds_bf16.hpp"
-#include "brg_conv1x1_ring_bf16.hpp"
 #include "brg_conv_small_bf16.hpp"
 #include "brg_conv_stem_bf16.hpp"
 #include "brg_conv_wgt.hpp"
@@ -619,33 +618,6 @@ static int conv1x1_bf16_launch(const ConvView &v, const void *I, const void *Wt,
     while (KW > 1 && waves(KW, PG) < 2048) KW >>= 1;
     if (knobs().conv_1x1_kw.set) { int x = knobs().conv_1x1_kw.val; if (x == 1 || x == 2 || x == 4) KW = x; }   // tuning knobs
     if (knobs().conv_1x1_pg.set) { int x = knobs().conv_1x1_pg.val; if (x == 2 || x == 4) PG = x; }
-    // at least 256 channels: the persistent ring-staged workgroup GEMM
-    {
-        bool ring = v.Cb >= 16 && v.Cb % 4 == 0 && knobs().conv_1x1_ring.on();
-        if (ring) {
-            a.tiles_x = (int)((npix + 127) / 128);
-            a.tiles_y = (v.Kb + 7) / 8;
-            a.tiles = a.tiles_x * a.tiles_y;
-            a.inv_tiles_x = 1.0f / (float)a.tiles_x;
-            a.inv_tiles_y = 1.0f / (float)a.tiles_y;
-            a.pixel_major = npix * v.Cb * 32 * v.sub > (int64_t)v.Kb * v.Cb * 512;
-            if (knobs().conv_1x1_lds_pm.set) a.pixel_major = knobs().conv_1x1_lds_pm.val != 0;   // tuning knob
-            static thread_local int ncu_dev = -1, ncu = 0;
-            int dev = 0;
-            hipError_t e = hipGetDevice(&dev);
-            if (e == hipSuccess && dev != ncu_dev) {
-                e = hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev);
-                if (e == hipSuccess) e = hipFuncSetAttribute((const void *)conv1x1_ring_bf16<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C1R_SMEM);
-                if (e == hipSuccess) e = hipFuncSetAttribute((const void *)conv1x1_ring_bf16<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C1R_SMEM);
-                if (e == hipSuccess) ncu_dev = dev;
-            }
-            if (e != hipSuccess) return fail(BRG_EHIP, "brg_conv (1x1 bf16, ring) set-up: %s", hipGetErrorString(e));
-            const dim3 g1((unsigned)(a.tiles < ncu ? a.tiles : ncu));
-            if (wtr) hipLaunchKernelGGL(conv1x1_ring_bf16<true>, g1, dim3(256), C1R_SMEM, s, a);
-            else hipLaunchKernelGGL(conv1x1_ring_bf16<false>, g1, dim3(256), C1R_SMEM, s, a);
-            return check_launch("brg_conv (1x1 bf16, ring) launch");
-        }
-    }
     // long reduction on few pixels: the workgroup-tiled kernel (operands shared through LDS), when all its
     // workgroups are resident at once (two per CU); with at most half as many 128 x 128 tiles as CUs, 128 x 64 tiles
     {

@@ -40,7 +40,6 @@ static void load_knobs()
     BRG_KNOB(conv_1x1_lds_pm, "BRG_CONV_1X1_LDS_PM");
     BRG_KNOB(conv_1x1_split, "BRG_CONV_1X1_SPLIT");
     BRG_KNOB(conv_1x1_wf, "BRG_CONV_1X1_WF");
-    BRG_KNOB(conv_1x1_ring, "BRG_CONV_1X1_RING");
     BRG_KNOB(conv_small, "BRG_CONV_SMALL");
     BRG_KNOB(conv_small_kw, "BRG_CONV_SMALL_KW");
     BRG_KNOB(conv_small_pg, "BRG_CONV_SMALL_PG");

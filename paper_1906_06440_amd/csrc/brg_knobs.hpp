@@ -15,7 +15,7 @@ struct Knob {
 struct Knobs {
     // name in the environment = BRG_ + the upper-case field name
     Knob conv_general, conv_pitch, conv_plane_pad, conv_kw, conv_no1x1, conv_zerofill, conv_nofuse;
-    Knob conv_1x1_kw, conv_1x1_pg, conv_1x1_lds, conv_1x1_lds_ngw, conv_1x1_lds_pm, conv_1x1_split, conv_1x1_wf, conv_1x1_ring;
+    Knob conv_1x1_kw, conv_1x1_pg, conv_1x1_lds, conv_1x1_lds_ngw, conv_1x1_lds_pm, conv_1x1_split, conv_1x1_wf;
     Knob conv_small, conv_small_kw, conv_small_pg, conv_small_gz;
     Knob conv_stem_classes, conv_stem_gx;
     Knob conv_wgt_general, conv_wgt_ps, conv_wgt_target;

@@ -212,8 +212,8 @@ extern "C" int brg_lstm_bwd(const brg_lstm_desc_t *desc, brg_dtype_t dtype, cons
                 "brg_lstm_bwd: blocking (%lld,%lld) does not divide (C,K)=(%lld,%lld)", (long long)desc->bc, (long long)desc->bk,
                 (long long)desc->C, (long long)desc->K);
     BRG_REQUIRE(desc->T < (1 << 20) && desc->N < (1 << 20) && desc->C < (1 << 20) && desc->K < (1 << 20) &&
-                    desc->T * desc->N < (1ll << 30),
-                BRG_EINVAL, "brg_lstm_bwd: size too large");
+                    desc->T * desc->N < (1ll << 30) && desc->N * desc->K < (1ll << 30) && desc->N * desc->C < (1ll << 30),
+                BRG_EINVAL, "brg_lstm_bwd: size too large");   // (N*K and N*C are 32-bit element counts of the kernels)
     BRG_REQUIRE(valid_dtype(dtype), BRG_EINVAL, "brg_lstm_bwd: bad dtype");
     BRG_REQUIRE(dtype == BRG_F32, BRG_EUNSUPPORTED, "brg_lstm_bwd: only fp32 is supported");
     BRG_REQUIRE(x && W4 && R4 && h && s && gates && dh && ws, BRG_EINVAL,

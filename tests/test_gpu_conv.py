@@ -127,7 +127,7 @@ ONE_BY_ONE = [(2, 32, 7, 16, 1), (3, 64, 14, 272, 1), (1, 256, 5, 80, 1), (2, 96
               (2, 128, 11, 144, 2)]
 
 
-@pytest.mark.parametrize("KW,PG", [(4, 4), (2, 4), (1, 4), (4, 2), (2, 2), (1, 2), (0, 0), (-1, -1), (-2, -2), (-3, -3), (-4, -4)])
+@pytest.mark.parametrize("KW,PG", [(4, 4), (2, 4), (1, 4), (4, 2), (2, 2), (1, 2), (0, 0), (-1, -1), (-2, -2), (-3, -3)])
 @pytest.mark.parametrize("N,C,H,K,stride", ONE_BY_ONE + [(2, 512, 7, 64, 1), (1, 544, 5, 32, 1), (2, 256, 14, 272, 1),
                                                          (3, 160, 9, 256, 2), (5, 320, 14, 400, 1), (3, 1024, 7, 144, 1), (4, 256, 13, 128, 2)])
 def test_conv1x1_bf16_streaming(monkeypatch, N, C, H, K, stride, KW, PG):
@@ -138,8 +138,6 @@ def test_conv1x1_bf16_streaming(monkeypatch, N, C, H, K, stride, KW, PG):
         monkeypatch.setenv("BRG_CONV_1X1_SPLIT", "0")
     elif KW == -1:
         monkeypatch.setenv("BRG_CONV_1X1_SPLIT", "1")    # the variant that splits the reduction between waves
-    elif KW == -4:                                       # the persistent ring-staged variant (C a multiple of 64 from 256, else as (0, 0))
-        monkeypatch.setenv("BRG_CONV_1X1_RING", "1")
     elif KW <= -2:                                       # the workgroup-tiled variant (C a multiple of 128, else as (0, 0))
         monkeypatch.setenv("BRG_CONV_1X1_LDS", "1")
         monkeypatch.setenv("BRG_CONV_1X1_LDS_NGW", "4" if KW == -2 else "2")
