@@ -276,26 +276,31 @@ def make_cfg4_variant(N=64, bf16=False):
     return fn, 50 * 2.0 * N * 4 * 1024 * 2048, "bf16" if bf16 else "f32", "LSTM fwd T=50 N=%d C=K=1024, %s" % (N, "bf16 operands, fp32 state" if bf16 else "fp32")
 
 
-def make_cfg4_bwd():
-    """Context row: backward pass of the cfg4 LSTM layer (dx, dW, dR, db from a random dh), fp32; the forward
-    results it differentiates are computed once outside the timed region.  Flops: twice the forward's."""
+def make_cfg4_bwd(bf16=False):
+    """Context row: backward pass of the cfg4 LSTM layer (dx, dW, dR, db from a random dh); the forward
+    results it differentiates are computed once outside the timed region.  Flops: twice the forward's.
+    bf16: x, W4, R4 and h are bf16, the pass widens them and runs in fp32."""
     import torch
     import paper_1906_06440_amd as brg
     import workloads as wl
     x, W4, R4, _ = wl.cfg4_lstm()
-    dx, dW, dR = _dev(x), _dev(W4), _dev(R4)
-    h, s = torch.empty((50, 64, 1024), device="cuda"), torch.empty((50, 64, 1024), device="cuda")
+    dt = brg.BF16 if bf16 else brg.F32
+    dx, dW, dR = _dev(x, bf16), _dev(W4, bf16), _dev(R4, bf16)
+    h = torch.empty((50, 64, 1024), device="cuda", dtype=torch.bfloat16 if bf16 else torch.float32)
+    s = torch.empty((50, 64, 1024), device="cuda")
     g = torch.empty((4, 50, 64, 1024), device="cuda")
     desc = brg.LstmDesc(50, 64, 1024, 1024, 16, 64, 64)
     ws = torch.zeros(64, dtype=torch.uint8, device="cuda")
-    brg.brg_lstm_fwd(desc, brg.F32, dx, dW, dR, None, None, None, h, s, g, ws)
+    brg.brg_lstm_fwd(desc, dt, dx, dW, dR, None, None, None, h, s, g, ws)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(4)
     dh = torch.rand((50, 64, 1024), device="cuda", generator=gen) * 0.2 - 0.1
-    gx, gW, gR, gb = torch.empty_like(dx), torch.empty_like(dW), torch.empty_like(dR), torch.empty((4, 1024), device="cuda")
-    wsb = torch.empty(brg.brg_lstm_bwd_ws_bytes(desc), dtype=torch.uint8, device="cuda")
-    fn = lambda: brg.brg_lstm_bwd(desc, brg.F32, dx, dW, dR, None, None, h, s, g, dh, None, gx, gW, gR, gb, None, None, wsb)
-    return fn, 2 * 50 * 2.0 * 64 * 4 * 1024 * 2048, "f32", "cfg4 backward: LSTM bwd (dx, dW, dR, db) T=50 N=64 C=K=1024, fp32"
+    f32 = dict(device="cuda", dtype=torch.float32)
+    gx, gW, gR, gb = torch.empty(dx.shape, **f32), torch.empty(dW.shape, **f32), torch.empty(dR.shape, **f32), torch.empty((4, 1024), **f32)
+    wsb = torch.empty(brg.brg_lstm_bwd_ws_bytes_dtype(desc, dt), dtype=torch.uint8, device="cuda")
+    fn = lambda: brg.brg_lstm_bwd(desc, dt, dx, dW, dR, None, None, h, s, g, dh, None, gx, gW, gR, gb, None, None, wsb)
+    return fn, 2 * 50 * 2.0 * 64 * 4 * 1024 * 2048, "f32", "cfg4 backward: LSTM bwd (dx, dW, dR, db) T=50 N=64 C=K=1024, %s" % (
+        "bf16 operands widened, fp32 arithmetic" if bf16 else "fp32")
 
 
 HBM_BYTES_PER_S = 8.0e12        # MI355X HBM3E peak
@@ -407,7 +412,8 @@ def run_cfg5(steps, warmup, N=64, use_graph=True, with_upd=False, only=None, col
 
 
 MAKERS = {"cfg4_bf16": lambda: make_cfg4_variant(64, True), "cfg4_n168": lambda: make_cfg4_variant(168, False),
-          "cfg4_n168_bf16": lambda: make_cfg4_variant(168, True), "cfg1": make_cfg1, "cfg1_ptrs": make_cfg1_ptrs, "cfg1_bf16": make_cfg1_bf16, "cfg2": make_cfg2, "cfg3": make_cfg3, "cfg4": make_cfg4, "cfg3_bf16": make_cfg3_bf16, "cfg4_bwd": make_cfg4_bwd}
+          "cfg4_n168_bf16": lambda: make_cfg4_variant(168, True), "cfg1": make_cfg1, "cfg1_ptrs": make_cfg1_ptrs, "cfg1_bf16": make_cfg1_bf16, "cfg2": make_cfg2, "cfg3": make_cfg3, "cfg4": make_cfg4, "cfg3_bf16": make_cfg3_bf16, "cfg4_bwd": make_cfg4_bwd,
+          "cfg4_bwd_bf16": lambda: make_cfg4_bwd(True)}
 
 
 def cpu_baseline_cfg2():
@@ -464,7 +470,7 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg1_ptrs", "cfg1_bf16", "cfg2", "cfg3", "cfg4", "cfg5", "cfg3_bf16", "cfg4_bwd", "cfg4_bf16", "cfg4_n168",
-                             "cfg4_n168_bf16", "copy"])
+                             "cfg4_n168_bf16", "cfg4_bwd_bf16", "copy"])
     ap.add_argument("--batch", type=int, default=None,
                     help="minibatch of cfg2 / cfg3 / cfg5 instead of the configured one (context rows: the paper's own "
                          "28 / 1344, inference at 1); such a line carries no others and no cpu_baseline")
@@ -540,7 +546,7 @@ def main():
         line["roofline"]["traffic"], line["roofline"]["traffic_source"] = measured_traffic(args.workload)
     if not args.no_others:
         others = {}
-        for key in ("cfg1", "cfg1_ptrs", "cfg1_bf16", "cfg2", "cfg3", "cfg4", "cfg3_bf16", "cfg4_bwd", "cfg4_bf16", "cfg4_n168", "cfg4_n168_bf16"):
+        for key in ("cfg1", "cfg1_ptrs", "cfg1_bf16", "cfg2", "cfg3", "cfg4", "cfg3_bf16", "cfg4_bwd", "cfg4_bwd_bf16", "cfg4_bf16", "cfg4_n168", "cfg4_n168_bf16"):
             if key == args.workload:
                 continue
             f2, fl2, dt2, nm2 = MAKERS[key]()

@@ -291,13 +291,16 @@ int brg_lstm_fwd(const brg_lstm_desc_t *desc, brg_dtype_t dtype, const void *x, 
  * Per time step, from the last to the first: the gate gradients dz_g are element-wise in the stored
  * gates and states, and dh_{t-1} += sum_g R_g^T dz_g is one batch-reduce chain of 4 K/bk weight
  * blocks per output block; dx, dW4, dR4 and db4 are sums over all time steps computed afterwards.
- * `ws`: DEVICE memory, 16-byte aligned, at least brg_lstm_bwd_ws_bytes(desc) bytes (the dz of all
- * steps and seventeen [N][K] buffers), contents undefined afterwards; required.  fp32 only (BRG_BF16 returns
- * BRG_EUNSUPPORTED: the bf16 layer has a forward pass only in this build).  Correct for every
- * shape; with bc = bk = 64 and N a multiple of 64 the GEMMs run on the kernel for 64 x 64 x 64 blocks,
- * otherwise on the general one.
+ * `ws`: DEVICE memory, 16-byte aligned, at least brg_lstm_bwd_ws_bytes_dtype(desc, dtype) bytes (the dz
+ * of all steps and seventeen [N][K] buffers; with bf16 operands also their fp32 copies), contents undefined
+ * afterwards; required.  BRG_BF16: x, W4, R4, h0 and h are bf16 (as brg_lstm_fwd takes and leaves them), every
+ * other tensor and every gradient is fp32; the operands are widened exactly into the workspace and the whole
+ * pass runs in fp32 arithmetic (no gradient is rounded to bf16).  Correct for every shape; with
+ * bc = bk = 64 and N a multiple of 64 the GEMMs run on the kernel for 64 x 64 x 64 blocks, otherwise on the
+ * general one.
  * ------------------------------------------------------------------------ */
-int64_t brg_lstm_bwd_ws_bytes(const brg_lstm_desc_t *desc);
+int64_t brg_lstm_bwd_ws_bytes(const brg_lstm_desc_t *desc);   /* the fp32 layer */
+int64_t brg_lstm_bwd_ws_bytes_dtype(const brg_lstm_desc_t *desc, brg_dtype_t dtype);
 
 int brg_lstm_bwd(const brg_lstm_desc_t *desc, brg_dtype_t dtype, const void *x, const void *W4,
                  const void *R4, const void *h0, const void *s0, const void *h, const void *s,

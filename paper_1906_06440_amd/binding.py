@@ -18,7 +18,7 @@ __all__ = [
     "ConvDesc", "FcDesc", "LstmDesc",
     "brg_gemm", "brg_gemm_strided", "brg_conv_ws_bytes", "brg_conv_fwd", "brg_conv_bwd_data", "brg_conv_bwd_wgt",
     "brg_conv_bwd_wgt_ws_bytes", "brg_fc_fwd", "brg_fc_bwd", "brg_fc_bwd_chain", "brg_lstm_fwd", "brg_lstm_bwd",
-    "brg_lstm_bwd_ws_bytes", "brg_conv_bwd_wgt_noalloc", "brg_tuning_reload", "CONV_BWD_WGT_NOALLOC_MAX_BYTES", "EXPORTS",
+    "brg_lstm_bwd_ws_bytes", "brg_lstm_bwd_ws_bytes_dtype", "brg_conv_bwd_wgt_noalloc", "brg_tuning_reload", "CONV_BWD_WGT_NOALLOC_MAX_BYTES", "EXPORTS",
 ]
 
 F32, BF16 = 0, 1
@@ -29,7 +29,7 @@ _STATUS = {0: "BRG_OK", 1: "BRG_EINVAL", 2: "BRG_EALIGN", 3: "BRG_EUNSUPPORTED",
 EXPORTS = [
     "brg_last_error", "brg_version", "brg_gemm", "brg_gemm_strided", "brg_conv_ws_bytes", "brg_conv_fwd",
     "brg_conv_bwd_data", "brg_conv_bwd_wgt", "brg_conv_bwd_wgt_ws_bytes", "brg_fc_fwd", "brg_fc_bwd", "brg_fc_bwd_chain",
-    "brg_lstm_fwd", "brg_lstm_bwd", "brg_lstm_bwd_ws_bytes", "brg_conv_bwd_wgt_noalloc", "brg_tuning_reload",
+    "brg_lstm_fwd", "brg_lstm_bwd", "brg_lstm_bwd_ws_bytes", "brg_lstm_bwd_ws_bytes_dtype", "brg_conv_bwd_wgt_noalloc", "brg_tuning_reload",
 ]
 CONV_BWD_WGT_NOALLOC_MAX_BYTES = 72 * 1024 * 1024
 
@@ -91,13 +91,15 @@ def load():
     lib.brg_lstm_fwd.argtypes = [C.POINTER(LstmDesc), ci, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.brg_lstm_bwd.argtypes = [C.POINTER(LstmDesc), ci] + [vp] * 18
     lib.brg_lstm_bwd_ws_bytes.argtypes = [C.POINTER(LstmDesc)]
+    lib.brg_lstm_bwd_ws_bytes_dtype.argtypes = [C.POINTER(LstmDesc), ci]
     for name in EXPORTS:
         if name not in ("brg_last_error", "brg_version", "brg_conv_ws_bytes", "brg_conv_bwd_wgt_ws_bytes",
-                        "brg_lstm_bwd_ws_bytes", "brg_tuning_reload"):
+                        "brg_lstm_bwd_ws_bytes", "brg_lstm_bwd_ws_bytes_dtype", "brg_tuning_reload"):
             getattr(lib, name).restype = ci
     lib.brg_conv_ws_bytes.restype = i64
     lib.brg_conv_bwd_wgt_ws_bytes.restype = i64
     lib.brg_lstm_bwd_ws_bytes.restype = i64
+    lib.brg_lstm_bwd_ws_bytes_dtype.restype = i64
     _lib = lib
     return lib
 
@@ -203,6 +205,10 @@ def brg_lstm_fwd(desc: LstmDesc, dtype, x, W4, R4, b4, h0, s0, h, s, gates=None,
 
 def brg_lstm_bwd_ws_bytes(desc: LstmDesc) -> int:
     return int(load().brg_lstm_bwd_ws_bytes(C.byref(desc)))
+
+
+def brg_lstm_bwd_ws_bytes_dtype(desc: LstmDesc, dtype) -> int:
+    return int(load().brg_lstm_bwd_ws_bytes_dtype(C.byref(desc), dtype))
 
 
 def brg_lstm_bwd(desc: LstmDesc, dtype, x, W4, R4, h0, s0, h, s, gates, dh, ds_last, dx, dW4, dR4, db4, dh0, ds0, ws,

@@ -191,12 +191,36 @@ __global__ __launch_bounds__(256) void lstm_bwd_copy(float *dst, const float *sr
     if (e < n) dst[e] = src ? src[e] : 0.f;
 }
 
+// bf16 operands of the backward pass are widened (exactly) to fp32 copies in the workspace: four elements per thread
+__global__ __launch_bounds__(256) void lstm_bwd_widen(const bf16_t *src, float *dst, int64_t n)
+{
+    const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (e + 3 < n) {
+        const us4v v = *(const us4v *)(src + e);
+        *(float4v *)(dst + e) = float4v{to_f32<bf16_t>(v[0]), to_f32<bf16_t>(v[1]), to_f32<bf16_t>(v[2]), to_f32<bf16_t>(v[3])};
+    } else {
+        for (int64_t i = e; i < n; ++i) dst[i] = to_f32<bf16_t>(src[i]);
+    }
+}
+
+static int64_t pad16(int64_t bytes) { return (bytes + 15) & ~(int64_t)15; }
+
 }  // namespace brg
 
 extern "C" int64_t brg_lstm_bwd_ws_bytes(const brg_lstm_desc_t *desc)
 {
     if (!desc || desc->T <= 0 || desc->N <= 0 || desc->K <= 0) return 0;
     return (4 * desc->T + 17) * desc->N * desc->K * 4;     // dz [T][N][4K], sixteen partial dh_rec [N][K], ds [N][K]
+}
+
+extern "C" int64_t brg_lstm_bwd_ws_bytes_dtype(const brg_lstm_desc_t *desc, brg_dtype_t dtype)
+{
+    const int64_t base = brg_lstm_bwd_ws_bytes(desc);
+    if (base == 0 || dtype != BRG_BF16 || desc->C <= 0) return base;
+    // + fp32 copies of x, W4, R4, h and h0
+    const int64_t T = desc->T, N = desc->N, C = desc->C, K = desc->K;
+    return brg::pad16(base) + brg::pad16(T * N * C * 4) + brg::pad16(4 * K * C * 4) + brg::pad16(4 * K * K * 4) + brg::pad16(T * N * K * 4) +
+           brg::pad16(N * K * 4);
 }
 
 extern "C" int brg_lstm_bwd(const brg_lstm_desc_t *desc, brg_dtype_t dtype, const void *x, const void *W4, const void *R4,
@@ -215,7 +239,6 @@ extern "C" int brg_lstm_bwd(const brg_lstm_desc_t *desc, brg_dtype_t dtype, cons
                     desc->T * desc->N < (1ll << 30) && desc->N * desc->K < (1ll << 30) && desc->N * desc->C < (1ll << 30),
                 BRG_EINVAL, "brg_lstm_bwd: size too large");   // (N*K and N*C are 32-bit element counts of the kernels)
     BRG_REQUIRE(valid_dtype(dtype), BRG_EINVAL, "brg_lstm_bwd: bad dtype");
-    BRG_REQUIRE(dtype == BRG_F32, BRG_EUNSUPPORTED, "brg_lstm_bwd: only fp32 is supported");
     BRG_REQUIRE(x && W4 && R4 && h && s && gates && dh && ws, BRG_EINVAL,
                 "brg_lstm_bwd: null tensor (x, W4, R4, h, s, gates, dh and ws are required)");
     BRG_REQUIRE(aligned16(x) && aligned16(W4) && aligned16(R4) && aligned16(h0) && aligned16(s0) && aligned16(h) && aligned16(s) &&
@@ -229,6 +252,24 @@ extern "C" int brg_lstm_bwd(const brg_lstm_desc_t *desc, brg_dtype_t dtype, cons
     const int NK = d.N * d.K;
     const int64_t TNK = (int64_t)d.T * NK;
     float *dz = (float *)ws, *dh_rec = dz + 4 * TNK, *dsb = dh_rec + 16 * (int64_t)NK;   // dh_rec: up to sixteen partial sums
+    if (dtype == BRG_BF16) {
+        // x, W4, R4, h, h0 arrive in bf16: the pass runs in fp32 on exact fp32 copies of them (no gradient is rounded to
+        // bf16 anywhere); the copies follow the fp32 workspace
+        char *p = (char *)ws + pad16(brg_lstm_bwd_ws_bytes(desc));
+        const void **srcs[5] = {&x, &W4, &R4, &h, &h0};
+        const int64_t counts[5] = {(int64_t)d.T * d.N * d.C, (int64_t)4 * d.K * d.C, (int64_t)4 * d.K * d.K, TNK, (int64_t)NK};
+        for (int i = 0; i < 5; ++i) {
+            if (*srcs[i]) {
+                const int64_t nthr = (counts[i] + 3) / 4;
+                hipLaunchKernelGGL(lstm_bwd_widen, dim3((unsigned)((nthr + 255) / 256)), dim3(256), 0, st, (const bf16_t *)*srcs[i], (float *)p,
+                                   counts[i]);
+                int rcw = check_launch("brg_lstm_bwd (bf16 operands to fp32) launch");
+                if (rcw) return rcw;
+                *srcs[i] = p;
+            }
+            p += pad16(counts[i] * 4);
+        }
+    }
     // 64-wide blocks and whole 64-row batch tiles: the GEMMs run on the 64 x 64 x 64 multi-job kernel
     const bool fast = d.bc == 64 && d.bk == 64 && d.N % 64 == 0 && (int64_t)4 * d.K * d.K < (1ll << 31) && !knobs().lstm_general.set;
     const float *hf = (const float *)h, *sf = (const float *)s, *gf = (const float *)gates, *dhf = (const float *)dh;

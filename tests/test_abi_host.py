@@ -107,7 +107,12 @@ def test_lstm_bwd_and_workspace_queries_validation(lib):
     assert lib.brg_lstm_bwd_ws_bytes(C.byref(ld)) == (4 * 2 + 17) * 4 * 64 * 4
     assert lib.brg_lstm_bwd_ws_bytes(None) == 0
     args = [A16] * 9 + [None] + [A16] * 3 + [None] * 3 + [A16, None]       # x .. dh, ds_last, dx dW4 dR4, db4 dh0 ds0, ws, stream
-    assert lib.brg_lstm_bwd(C.byref(ld), 1, *args) == brg.EUNSUPPORTED      # bf16
+    lib.brg_lstm_bwd_ws_bytes_dtype.restype = C.c_int64
+    base = (4 * 2 + 17) * 4 * 64 * 4
+    assert lib.brg_lstm_bwd_ws_bytes_dtype(C.byref(ld), 0) == base
+    # bf16: + fp32 copies of x [2][4][64], W4 and R4 [4][64][64], h [2][4][64], h0 [4][64]
+    assert lib.brg_lstm_bwd_ws_bytes_dtype(C.byref(ld), 1) == base + 4 * (2 * 4 * 64 + 2 * 4 * 64 * 64 + 2 * 4 * 64 + 4 * 64)
+    assert lib.brg_lstm_bwd(C.byref(ld), 7, *args) == brg.EINVAL            # bad dtype
     bad = list(args)
     bad[16] = None                                                           # no workspace
     assert lib.brg_lstm_bwd(C.byref(ld), 0, *bad) == brg.EINVAL

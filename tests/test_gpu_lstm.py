@@ -74,9 +74,12 @@ def test_config4_full_size():
                                            (1, 3, 8, 8, 8, 8), (6, 32, 192, 256, 64, 64), (10, 64, 128, 128, 64, 64), (3, 128, 64, 320, 64, 64),
                                            (2, 64, 192, 64, 64, 64)])
 @pytest.mark.parametrize("full", [True, False])
-def test_lstm_backward(T, N, C, K, bc, bk, full):
+@pytest.mark.parametrize("dtype", [brg.F32, brg.BF16])
+def test_lstm_backward(T, N, C, K, bc, bk, full, dtype):
     """Backward pass on the forward results the GPU stored (so both sides differentiate the same point): all six
-    gradients with initial states and a gradient on the final cell state, or only dx / dW / dR from zero states."""
+    gradients with initial states and a gradient on the final cell state, or only dx / dW / dR from zero states.
+    bf16: x, W4, R4, h0 and h are bf16 (h as the bf16 forward pass left it), the pass itself runs in fp32 on
+    exactly those values, so the fp32 bound applies."""
     x, W4, R4, b4 = wl.cfg4_lstm(T, N, C, K, bc, bk, with_bias=True, seed_extra=T + N)
     W4 *= 4.0
     R4 *= 4.0
@@ -86,17 +89,20 @@ def test_lstm_backward(T, N, C, K, bc, bk, full):
     dh = wl.uniform(rng, (T, N, K))
     ds_last = wl.uniform(rng, (N, K)) if full else None
     d = orc.LstmShape(T, N, C, K, 16, bc, bk)
-    h, s, g = gpu_lstm(d, x, W4, R4, b4=b4, h0=h0, s0=s0)
+    h, s, g = gpu_lstm(d, x, W4, R4, b4=b4, h0=h0, s0=s0, dtype=dtype)
     desc = brg.LstmDesc(T, N, C, K, 16, bc, bk)
-    opt = lambda a: None if a is None else dev(a)
+    opt = lambda a, dt=brg.F32: None if a is None else dev(a, dt)
     dx, dW4, dR4 = empty((T, N, C)), empty(d.w_shape), empty(d.r_shape)
     db4 = empty((4, K)) if full else None
     dh0 = empty((N, K)) if full else None
     ds0 = empty((N, K)) if full else None
-    ws = workspace(brg.brg_lstm_bwd_ws_bytes(desc))
-    brg.brg_lstm_bwd(desc, brg.F32, dev(x), dev(W4), dev(R4), opt(h0), opt(s0), dev(h), dev(s), dev(g), dev(dh), opt(ds_last),
-                     dx, dW4, dR4, db4, dh0, ds0, ws)
+    assert brg.brg_lstm_bwd_ws_bytes_dtype(desc, brg.F32) == brg.brg_lstm_bwd_ws_bytes(desc)
+    ws = workspace(brg.brg_lstm_bwd_ws_bytes_dtype(desc, dtype))
+    brg.brg_lstm_bwd(desc, dtype, dev(x, dtype), dev(W4, dtype), dev(R4, dtype), opt(h0, dtype), opt(s0), dev(h, dtype), dev(s), dev(g),
+                     dev(dh), opt(ds_last), dx, dW4, dR4, db4, dh0, ds0, ws)
     torch.cuda.synchronize()
+    x, W4, R4 = (as_seen_by_gpu(v, dtype) for v in (x, W4, R4))
+    h0 = None if h0 is None else as_seen_by_gpu(h0, dtype)
     rx, rW, rR, rb, rh0, rs0 = orc.lstm_bwd(d, x, W4, R4, h0, s0, h, s, g, dh, ds_last)
     wd = _bwd_widen(T)
     check(host(dx), rx, brg.F32, "dx", widen=wd)
