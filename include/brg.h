@@ -63,6 +63,8 @@ const char *brg_version(void);
  *   BRG_FC_GENERAL (flag), BRG_FC_WGT_GENERAL (flag), BRG_FC_G64 = 64|32, BRG_FC_G128 = 0|1
  *                             fully connected layers: general kernel / tile shape of the tuned ones
  *   BRG_LSTM_GENERAL (flag)   LSTM forward and backward: one general launch per time step
+ *   BRG_LSTM_SPIN_LIMIT = n   resident LSTM kernel: polls of the step barrier before a workgroup gives up (0: at once;
+ *                             a test's way to reach the give-up path with every wave still exiting normally)
  *   BRG_CONV_GENERAL (flag), BRG_CONV_NO1X1 (flag), BRG_CONV_WGT_GENERAL (flag)
  *                             convolutions: general kernel for all / for 1x1 layers / for the weight gradient
  *   BRG_CONV_KW = 1|2, BRG_CONV_PITCH = 0, BRG_CONV_PLANE_PAD = bytes, BRG_CONV_ZEROFILL (flag), BRG_CONV_NOFUSE (flag)

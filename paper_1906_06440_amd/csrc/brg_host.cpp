@@ -56,6 +56,7 @@ static void load_knobs()
     BRG_KNOB(gemm_general, "BRG_GEMM_GENERAL");
     BRG_KNOB(no_ring, "BRG_NO_RING");
     BRG_KNOB(lstm_general, "BRG_LSTM_GENERAL");
+    BRG_KNOB(lstm_spin_limit, "BRG_LSTM_SPIN_LIMIT");
 #undef BRG_KNOB
 }
 

@@ -20,7 +20,7 @@ struct Knobs {
     Knob conv_stem_classes, conv_stem_gx;
     Knob conv_wgt_general, conv_wgt_ps, conv_wgt_target;
     Knob fc_general, fc_g64, fc_g128, fc_wgt_general;
-    Knob gemm_general, no_ring, lstm_general;
+    Knob gemm_general, no_ring, lstm_general, lstm_spin_limit;
     // presence alone switches these (any value, as before the table existed)
     bool flag(const Knob &k) const { return k.set; }
 };

@@ -278,6 +278,8 @@ extern "C" int brg_lstm_fwd(const brg_lstm_desc_t *desc, brg_dtype_t dtype, cons
         r.R4 = R4; r.h0 = h0; r.s0 = (const float *)s0;
         r.h = h; r.s = (float *)s; r.gates = (float *)gates; r.sync = (unsigned *)ws;
         r.T = d.T; r.N = d.N; r.K = d.K; r.spin_limit = 200000u * (unsigned)np;
+        // (tests force the give-up path from the host with a limit no wait can meet; every wave still exits normally)
+        if (knobs().lstm_spin_limit.set && knobs().lstm_spin_limit.val >= 0) r.spin_limit = (unsigned)knobs().lstm_spin_limit.val;
         // Should other work keep compute units busy for longer than the spin limit, the kernel gives up and
         // reports through sync[1]; the kernel enqueued after it then overwrites h, s and gates with NaN, so
         // that a run that gave up cannot pass for a result.

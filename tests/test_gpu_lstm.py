@@ -135,6 +135,35 @@ def test_config4_backward_full_size():
     check(host(db4), rb, brg.F32, "db4", widen=wd)
 
 
+def test_lstm_resident_kernel_gives_up_loudly(monkeypatch):
+    """The resident kernel's step barrier is a bounded wait.  With a limit of zero polls (set from the host) a
+    workgroup that has to wait at all gives up: every wave exits normally, word 1 of the workspace is set, and the
+    kernel enqueued behind it overwrites h, s and the gates with NaN, so the run cannot pass for a result.  The
+    next call with the default limit, on the same workspace, is correct again (the library clears the words)."""
+    T, N, C, K = 6, 64, 128, 1024
+    x, W4, R4, b4 = wl.cfg4_lstm(T, N, C, K, 64, 64, with_bias=True, seed_extra=3)
+    desc = brg.LstmDesc(T, N, C, K, 16, 64, 64)
+    h, s, g = empty((T, N, K)), empty((T, N, K)), empty((4, T, N, K))
+    ws = workspace(64)
+    monkeypatch.setenv("BRG_LSTM_SPIN_LIMIT", "0")
+    brg.brg_tuning_reload()
+    brg.brg_lstm_fwd(desc, brg.F32, dev(x), dev(W4), dev(R4), dev(b4), None, None, h, s, g, ws)
+    torch.cuda.synchronize()
+    gave_up = int(ws[:8].view(torch.int32)[1].item()) != 0
+    # 256 workgroups never all reach a barrier within zero polls of each other
+    assert gave_up, "the wait was expected to give up"
+    assert torch.isnan(h).all() and torch.isnan(s).all() and torch.isnan(g).all()
+    monkeypatch.delenv("BRG_LSTM_SPIN_LIMIT")
+    brg.brg_tuning_reload()
+    brg.brg_lstm_fwd(desc, brg.F32, dev(x), dev(W4), dev(R4), dev(b4), None, None, h, s, g, ws)
+    torch.cuda.synchronize()
+    assert int(ws[:8].view(torch.int32)[1].item()) == 0
+    d = orc.LstmShape(T, N, C, K, 16, 64, 64)
+    rh, rs, rg = orc.lstm_fwd(d, x, W4, R4, b4)
+    check(host(h), rh, brg.F32, "h after a give-up")
+    check(host(s), rs, brg.F32, "s after a give-up")
+
+
 def test_lstm_general_path_forced(monkeypatch):
     """BRG_LSTM_GENERAL: a shape of the resident / batched kernels on one general launch per time step."""
     monkeypatch.setenv("BRG_LSTM_GENERAL", "1")
