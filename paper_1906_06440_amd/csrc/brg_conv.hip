@@ -323,6 +323,8 @@ static ConvTilePlan plan_conv_tile(const ConvDims &d, bool bwd, bool bf16 = fals
         a.w_ob = d.R * d.S; a.w_ib = d.Cb * d.R * d.S;
     }
     if (a.Q > CT_NG * 16) return pl;
+    a.Hout = a.P; a.Wout = a.Q; a.osub = 1; a.ooh = 0; a.oow = 0;
+    for (int t = 0; t < d.R * d.S; ++t) a.wtap[t] = bwd ? d.R * d.S - 1 - t : t;
     a.Hv = (a.P - 1) * str + d.R;
     int wp = (a.Q - 1) * str + d.S;
     a.Wp = wp > a.W + a.pw ? wp : a.W + a.pw;
@@ -438,6 +440,90 @@ struct Bf16Plan {
     int key, KW;
     dim3 grid;
 };
+
+// fp32: one parity class of a strided backward-by-data pass (a stride-1 pass over dO with the class's taps,
+// results placed on every stride-th pixel) on the fp32 tiled kernel in its backward form
+static ConvTilePlan plan_view_f32(const ConvView &v)
+{
+    ConvTilePlan pl;
+    pl.ok = false;
+    const int taps = v.R * v.S;
+    if (v.str != 1 || v.sub != 1 || v.R > 2 || v.S > 2 || v.P <= 0 || v.Q <= 0 || v.Q > CT_NG * 16) return pl;
+    if ((int64_t)v.N * v.Cb * v.Hin * v.Win * 16 >= (1ll << 31) || (int64_t)v.N * v.Kb * v.Hout * v.Wout * 16 >= (1ll << 31)) return pl;
+    ConvTileArgs &a = pl.a;
+    a = ConvTileArgs{};
+    a.N = v.N; a.Cb = v.Cb; a.H = v.H; a.W = v.W; a.Kb = v.Kb; a.P = v.P; a.Q = v.Q; a.ph = v.ph; a.pw = v.pw;
+    a.sub = 1; a.Hin = v.Hin; a.Win = v.Win; a.w_ob = v.w_ob; a.w_ib = v.w_ib;
+    a.osub = v.osub; a.ooh = v.ooh; a.oow = v.oow; a.Hout = v.Hout; a.Wout = v.Wout;
+    for (int t = 0; t < 16; ++t) a.wtap[t] = v.wtap[t];
+    a.Hv = (a.P - 1) + v.R;
+    const int wp = (a.Q - 1) + v.S;
+    a.Wp = wp > a.W + a.pw ? wp : a.W + a.pw;
+    a.trg = (CT_NG * 16) / a.Q;
+    a.total_rows = a.N * a.P;
+    if (a.total_rows >= (1 << 22) || (int64_t)a.N * a.Hv >= (1 << 22)) return pl;
+    a.ntiles = (a.total_rows + a.trg - 1) / a.trg;
+    int nv_max = 0;
+    for (int tile = 0; tile < a.ntiles; ++tile) {
+        const int gr0 = tile * a.trg;
+        const int rows = a.total_rows - gr0 < a.trg ? a.total_rows - gr0 : a.trg;
+        const int vf = (gr0 / a.P) * a.Hv + (gr0 % a.P);
+        const int grl = gr0 + rows - 1;
+        const int nv = (grl / a.P) * a.Hv + (grl % a.P) + v.R - vf;
+        if (nv > nv_max) nv_max = nv;
+    }
+    const int chunks = nv_max * a.W * 4;
+    pl.R = v.R; pl.STR = 1; pl.KW = 1;
+    if (taps > 1) {
+        pl.CG = 1;
+        pl.NPASS = chunks <= 1024 ? 4 : 8;
+        if (chunks > 256 * pl.NPASS) return pl;
+    } else {
+        if (a.Cb % 4 == 0 && chunks <= 512) { pl.CG = 4; pl.NPASS = 2; }
+        else if (a.Cb % 2 == 0 && chunks <= 1024) { pl.CG = 2; pl.NPASS = 4; }
+        else return pl;
+    }
+    int plane = nv_max * a.Wp * 16;
+    plane = ((plane + 255) / 256) * 256 + conv_plane_pad();
+    a.plane_bytes = plane;
+    a.buf_bytes = pl.CG * 4 * plane;
+    pl.smem = 2 * (size_t)a.buf_bytes;
+    if (pl.smem > 80 * 1024) return pl;
+    a.inv_Q = 1.0f / a.Q; a.inv_P = 1.0f / a.P; a.inv_Hv = 1.0f / a.Hv; a.inv_W4 = 1.0f / (a.W * 4);
+    const int ktiles = (a.Kb + 3) / 4;
+    int gx = (512 / ktiles) & ~7;
+    if (gx < 8) gx = 8;
+    if (gx > a.ntiles) gx = a.ntiles;
+    pl.grid = dim3(gx, ktiles);
+    pl.ok = true;
+    return pl;
+}
+
+template <int R, int S, int CG, int NPASS> static int conv_tile_f32_view_go(ConvTilePlan &pl, hipStream_t s)
+{
+    auto kern = conv_tile_f32<R, S, 1, CG, NPASS, 1>;
+    int rc = allow_big_lds((const void *)kern, pl.smem);
+    if (rc) return rc;
+    hipLaunchKernelGGL(kern, pl.grid, dim3(256), pl.smem, s, pl.a);
+    return check_launch("brg_conv_bwd_data (tiled, parity class) launch");
+}
+
+static int conv_tile_f32_view_launch(ConvTilePlan &pl, int S, const void *dO, const void *Wt, void *dI, hipStream_t s)
+{
+    pl.a.I = dO; pl.a.Wt = Wt; pl.a.O = dI; pl.a.bias = nullptr; pl.a.act = BRG_ACT_NONE;
+    const int key = pl.R * 1000 + S * 100 + pl.CG * 10 + pl.NPASS;
+    switch (key) {
+    case 1142: return conv_tile_f32_view_go<1, 1, 4, 2>(pl, s);
+    case 1124: return conv_tile_f32_view_go<1, 1, 2, 4>(pl, s);
+    case 1214: return conv_tile_f32_view_go<1, 2, 1, 4>(pl, s);
+    case 1218: return conv_tile_f32_view_go<1, 2, 1, 8>(pl, s);
+    case 2114: return conv_tile_f32_view_go<2, 1, 1, 4>(pl, s);
+    case 2118: return conv_tile_f32_view_go<2, 1, 1, 8>(pl, s);
+    case 2214: return conv_tile_f32_view_go<2, 2, 1, 4>(pl, s);
+    case 2218: return conv_tile_f32_view_go<2, 2, 1, 8>(pl, s);
+    }
+    return fail(BRG_EUNSUPPORTED, "brg_conv_bwd_data: internal: no tiled fp32 kernel for key %d", key);
+}
 
 // `grids`: how many such views run as one grid (the fused parity classes of a strided backward pass)
 static Bf16Plan plan_view_bf16(const ConvView &v, int grids = 1)
@@ -1043,6 +1129,39 @@ extern "C" int brg_conv_bwd_data(const brg_conv_desc_t *desc, brg_dtype_t dtype,
         ConvTilePlan pl = plan_conv_tile(d, true);
         if (pl.ok && !knobs().conv_general.set)
             return conv_tile_f32_launch<1>(pl, dO, Wt, dI, nullptr, BRG_ACT_NONE, s);
+        // stride 2: one tiled pass per parity class of the input pixels; classes without a tap are zero-filled
+        if (d.sh == 2 && d.sw == 2 && !knobs().conv_general.set) {
+            ConvTilePlan plans[4];
+            int svals[4];
+            int np = 0;
+            bool all_ok = true, holes = false;
+            for (int ca = 0; ca < 2 && all_ok; ++ca)
+                for (int cb = 0; cb < 2 && all_ok; ++cb) {
+                    ConvView v;
+                    if (!conv_bwd_view(d, ca, cb, &v)) {
+                        if (ca < d.H && cb < d.W) holes = true;
+                        continue;
+                    }
+                    if (v.R == 99) { all_ok = false; break; }
+                    plans[np] = plan_view_f32(v);
+                    svals[np] = v.S;
+                    all_ok = plans[np].ok;
+                    ++np;
+                }
+            if (all_ok && np > 0) {
+                if (holes) {
+                    const int64_t n16 = (int64_t)d.N * d.C * d.H * d.W * 4 / 16;
+                    hipLaunchKernelGGL(conv_zero_fill, dim3(2048), dim3(256), 0, s, (float4v *)dI, n16);
+                    rc = check_launch("brg_conv_bwd_data (zero fill) launch");
+                    if (rc) return rc;
+                }
+                for (int i = 0; i < np; ++i) {
+                    rc = conv_tile_f32_view_launch(plans[i], svals[i], dO, Wt, dI, s);
+                    if (rc) return rc;
+                }
+                return BRG_OK;
+            }
+        }
         return conv_bwd_data_launch<float, float>(d, dO, Wt, dI, s);
     }
     if (dtype == BRG_BF16 && out_dtype == BRG_F32) return conv_bwd_data_launch<bf16_t, float>(d, dO, Wt, dI, s);

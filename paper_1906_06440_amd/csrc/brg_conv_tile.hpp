@@ -54,7 +54,7 @@ struct ConvTileArgs {
     int buf_bytes;     // planes per buffer * plane_bytes
     int w_ob, w_ib;    // weight block index = ob*w_ob + ib*w_ib + tap (in 16x16 blocks)
     float inv_Q, inv_P, inv_Hv, inv_W4;  // reciprocals for the index divisions
-    // (bf16 kernel) placement of the logical P x Q output inside the physical Hout x Wout tensor:
+    // placement of the logical P x Q output inside the physical Hout x Wout tensor:
     // output pixel (oj, oi) is stored at (oj*osub + ooh, oi*osub + oow); and the weight tap that
     // belongs to kernel tap t (identity forward, flipped / thinned out for backward by data)
     int osub, ooh, oow, Hout, Wout;
@@ -169,7 +169,8 @@ __global__ __launch_bounds__(256, 2) void conv_tile_f32(ConvTileArgs a)
     };
 
     // ---- weights: block (ob = kb, ib, tap) at Wt + (kb*w_ob + ib*w_ib + tap')*256, where
-    // tap' = tap for the forward pass and TAPS-1-tap (spatially flipped) for backward by data.
+    // tap' = tap for the forward pass and wtap[tap] for backward by data (spatially flipped; for the parity
+    // classes of a strided layer also thinned out to the taps of the class).
     // Lane (li, kg) needs, for MFMA step q, the element (row li, reduction index 4*kg + q):
     //   forward : block[c = 4kg+q][k = li]  -> four dwords 16 elements apart (one float4 from a transposed copy)
     //   backward: block[c = li][k = 4kg+q]  -> one aligned float4
@@ -183,7 +184,7 @@ __global__ __launch_bounds__(256, 2) void conv_tile_f32(ConvTileArgs a)
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) {
             const int tap = u % TAPS;
-            const float *src = wlane + ((int64_t)(sidx * CG + u / TAPS) * a.w_ib + (BWD ? TAPS - 1 - tap : tap)) * 256;
+            const float *src = wlane + ((int64_t)(sidx * CG + u / TAPS) * a.w_ib + (BWD ? a.wtap[tap] : tap)) * 256;
             if (WVEC) {
                 const float4v v = *(const float4v *)src;
 #pragma unroll
@@ -224,7 +225,7 @@ __global__ __launch_bounds__(256, 2) void conv_tile_f32(ConvTileArgs a)
                 const int n = fdiv(gr, a.P, a.inv_P), oj = gr - n * a.P;
                 const int lrow = n * a.Hv + oj * STR - v_first;
                 bbase[g] = kg * a.plane_bytes + (lrow * a.Wp + (ok ? oi : 0) * STR) * 16;
-                ooff[g] = (ok && kb_ok) ? (((n * a.Kb + kb) * a.P + oj) * a.Q + oi) * 16 + 4 * kg : -1;
+                ooff[g] = (ok && kb_ok) ? (((n * a.Kb + kb) * a.Hout + oj * a.osub + a.ooh) * a.Wout + oi * a.osub + a.oow) * 16 + 4 * kg : -1;
             }
         }
 

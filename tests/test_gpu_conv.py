@@ -177,6 +177,19 @@ def test_conv_small_bf16_variants(monkeypatch, N, C, H, K, R, stride, pad, KW, P
     check(gpu_bwd_data(d, dO, W, brg.BF16, brg.BF16), orc.conv_bwd_data(d, dOs, Ws, out_bf16=True), brg.BF16, "few-pixel bwd")
 
 
+# fp32 backward by data of strided layers: one pass of the fp32 tiled kernel per parity class of the input pixels
+# (3x3 stride 2: classes with 1x1, 1x2, 2x1 and 2x2 taps; 1x1 stride 2: one class and a zero fill), on even and
+# odd image sizes (classes of different sizes), ragged tiles, and a 56-pixel-wide image (the deeper halo copy plan)
+@pytest.mark.parametrize("N,C,H,K,R,stride,pad", [
+    (2, 64, 16, 128, 3, 2, 1), (3, 64, 9, 64, 3, 2, 1), (2, 32, 13, 64, 3, 2, 1), (2, 256, 12, 128, 1, 2, 0),
+    (3, 64, 7, 32, 1, 2, 0), (2, 32, 56, 32, 3, 2, 1), (1, 128, 28, 64, 3, 2, 1)])
+def test_conv_fp32_strided_backward_tiled(N, C, H, K, R, stride, pad):
+    I, W, dO = wl.conv_tensors(N, C, H, K, R, stride, pad, cfg_index=5, seed_extra=C + H, want_dO=True)
+    d = orc.ConvShape(N, C, H, H, K, R, R, stride, pad)
+    check(gpu_bwd_data(d, dO, W), orc.conv_bwd_data(d, dO, W), brg.F32, "fp32 strided bwd-data")
+    check(gpu_fwd(d, I, W), orc.conv_fwd(d, I, W), brg.F32, "fp32 strided fwd")
+
+
 def test_conv_bf16_stem_tiled():
     """7x7 stride-2 stem, C=3 zero-padded to one block: forward pairs adjacent taps inside an MFMA,
     backward by data runs as four parity classes with 3x3 .. 4x4 taps."""
