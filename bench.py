@@ -215,15 +215,15 @@ def make_cfg3(N=1024):
     return fn, 12 * 2.0 * N * 1024 ** 2, "f32", "cfg3: MLP 4 x FC 1024->1024 bias+ReLU, N=%d, fwd+bwd-data+wgt, fp32, 64^3 blocks" % N
 
 
-def make_cfg3_bf16(N=1024):
-    """Context row: the cfg3 MLP in bf16 on 16-wide blocks (bn = 64), forward with bias + ReLU and the chained
-    backward pass with the workspace that lets the masked last layer use the tuned kernels."""
+def make_cfg3_bf16(N=1024, blk=16):
+    """Context rows: the cfg3 MLP in bf16 on 16-wide blocks (bn = 64) or on cfg3's own 64-wide blocks, forward with
+    bias + ReLU and the chained backward pass with the workspace that lets the masked last layer use the tuned kernels."""
     import numpy as np
     import torch
     import paper_1906_06440_amd as brg
     import workloads as wl
-    X0, Ws, bs, dYl = wl.cfg3_mlp(N=N, bc=16, bk=16)
-    desc = brg.FcDesc(N, 1024, 1024, 64, 16, 16)
+    X0, Ws, bs, dYl = wl.cfg3_mlp(N=N, bc=blk, bk=blk)
+    desc = brg.FcDesc(N, 1024, 1024, 64, blk, blk)
     dWs, dbs = [_dev(w, True) for w in Ws], [_dev(b) for b in bs]
     acts = [_dev(X0, True)] + [torch.empty_like(_dev(X0, True)) for _ in range(4)]
     grads = [torch.empty_like(acts[0]) for _ in range(4)] + [_dev(dYl, True)]
@@ -239,7 +239,7 @@ def make_cfg3_bf16(N=1024):
             brg.brg_fc_bwd_chain(desc, brg.BF16, grads[l + 1], acts[l + 1] if last else None, acts[l], dWs[l],
                                  brg.ACT_RELU if last else brg.ACT_NONE,
                                  brg.ACT_RELU if l > 0 else brg.ACT_NONE, grads[l], dWg[l], dbg[l], ws)
-    return fn, 12 * 2.0 * N * 1024 ** 2, "bf16", "cfg3 in bf16: MLP 4 x FC 1024->1024 bias+ReLU, N=%d, fwd+bwd-data+wgt, bn=64 bc=bk=16" % N
+    return fn, 12 * 2.0 * N * 1024 ** 2, "bf16", "cfg3 in bf16: MLP 4 x FC 1024->1024 bias+ReLU, N=%d, fwd+bwd-data+wgt, bn=64 bc=bk=%d" % (N, blk)
 
 
 def make_cfg4():
@@ -413,7 +413,7 @@ def run_cfg5(steps, warmup, N=64, use_graph=True, with_upd=False, only=None, col
 
 MAKERS = {"cfg4_bf16": lambda: make_cfg4_variant(64, True), "cfg4_n168": lambda: make_cfg4_variant(168, False),
           "cfg4_n168_bf16": lambda: make_cfg4_variant(168, True), "cfg1": make_cfg1, "cfg1_ptrs": make_cfg1_ptrs, "cfg1_bf16": make_cfg1_bf16, "cfg2": make_cfg2, "cfg3": make_cfg3, "cfg4": make_cfg4, "cfg3_bf16": make_cfg3_bf16, "cfg4_bwd": make_cfg4_bwd,
-          "cfg4_bwd_bf16": lambda: make_cfg4_bwd(True)}
+          "cfg4_bwd_bf16": lambda: make_cfg4_bwd(True), "cfg3_bf16_b64": lambda: make_cfg3_bf16(1024, 64)}
 
 
 def cpu_baseline_cfg2():
@@ -469,8 +469,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg1_ptrs", "cfg1_bf16", "cfg2", "cfg3", "cfg4", "cfg5", "cfg3_bf16", "cfg4_bwd", "cfg4_bf16", "cfg4_n168",
-                             "cfg4_n168_bf16", "cfg4_bwd_bf16", "copy"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg1_ptrs", "cfg1_bf16", "cfg2", "cfg3", "cfg4", "cfg5", "cfg3_bf16", "cfg3_bf16_b64", "cfg4_bwd", "cfg4_bf16", "cfg4_n168",
+                             "cfg4_n168_bf16", "cfg4_bwd_bf16", "cfg3_bf16_b64", "copy"])
     ap.add_argument("--batch", type=int, default=None,
                     help="minibatch of cfg2 / cfg3 / cfg5 instead of the configured one (context rows: the paper's own "
                          "28 / 1344, inference at 1); such a line carries no others and no cpu_baseline")
@@ -546,7 +546,7 @@ def main():
         line["roofline"]["traffic"], line["roofline"]["traffic_source"] = measured_traffic(args.workload)
     if not args.no_others:
         others = {}
-        for key in ("cfg1", "cfg1_ptrs", "cfg1_bf16", "cfg2", "cfg3", "cfg4", "cfg3_bf16", "cfg4_bwd", "cfg4_bwd_bf16", "cfg4_bf16", "cfg4_n168", "cfg4_n168_bf16"):
+        for key in ("cfg1", "cfg1_ptrs", "cfg1_bf16", "cfg2", "cfg3", "cfg4", "cfg3_bf16", "cfg3_bf16_b64", "cfg4_bwd", "cfg4_bwd_bf16", "cfg4_bf16", "cfg4_n168", "cfg4_n168_bf16"):
             if key == args.workload:
                 continue
             f2, fl2, dt2, nm2 = MAKERS[key]()

@@ -8,6 +8,7 @@
 #include "brg_g64.hpp"
 #include "brg_g128.hpp"
 #include "brg_fc_wgt_bf16.hpp"
+#include "brg_h64.hpp"
 #include "brg_engine.hpp"
 
 namespace brg {
@@ -211,6 +212,34 @@ __global__ __launch_bounds__(256) void fc_dbias_kernel(FcDims d, const TIn *dY, 
     if (q == 0 && k < d.K) db[k] = (part[0][kl] + part[1][kl]) + (part[2][kl] + part[3][kl]);
 }
 
+// Bias gradient of a bf16 layer on 64-wide blocks (dZ already masked): db[k] = sum_n dZ[n][k].  One workgroup per
+// feature block; thread (row r = t / 8, piece p = t % 8) adds the 8 features of piece p over the rows r and r + 32
+// of every batch block (16-byte loads, several in flight), then the 32 row slices are added in a fixed order.
+__global__ __launch_bounds__(256) void fc_dbias_bf16_b64(const bf16_t *dZ, float *db, int Nb, int Kb)
+{
+    typedef unsigned short us8 __attribute__((ext_vector_type(8)));
+    __shared__ float part[32][65];
+    const int t = threadIdx.x, r = t >> 3, p = t & 7, kb = blockIdx.x;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const bf16_t *src = dZ + (int64_t)kb * 4096 + r * 64 + p * 8;
+    const int64_t nstride = (int64_t)Kb * 4096;
+#pragma unroll 4
+    for (int nb = 0; nb < Nb; ++nb) {
+        const us8 v0 = *(const us8 *)(src + nb * nstride), v1 = *(const us8 *)(src + nb * nstride + 32 * 64);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += bf16_to_f32(v0[e]) + bf16_to_f32(v1[e]);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part[r][p * 8 + e] = acc[e];
+    __syncthreads();
+    if (t < 64) {
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) sum += part[i][t];
+        db[kb * 64 + t] = sum;
+    }
+}
+
 static int fc_dims(const brg_fc_desc_t *desc, FcDims *d, const char *who)
 {
     BRG_REQUIRE(desc != nullptr, BRG_EINVAL, "%s: desc is null", who);
@@ -336,6 +365,18 @@ extern "C" int brg_fc_fwd(const brg_fc_desc_t *desc, brg_dtype_t dtype, brg_dtyp
         const brg_conv_desc_t c = fc_as_conv1x1(d);
         return brg_conv_fwd(&c, dtype, out_dtype, X, Wt, Y, bias, act, nullptr, stream);
     }
+    if (dtype == BRG_BF16 && fc_blocks_64(d)) {
+        // 64-wide bf16 blocks: the batch-reduce kernel on the bf16 matrix instruction, one workgroup per block of Y;
+        // W blocks [c][k] have the reduction index strided (transposing LDS reads), X blocks [n][c] contiguous
+        H64Args a = {};
+        a.A = (const bf16_t *)Wt; a.B = (const bf16_t *)X; a.C = Y; a.bias = bias; a.act = act;
+        a.tiles_m = d.Kb; a.tiles_n = d.Nb; a.chain = d.Cb; a.alpha = 1.f; a.beta = 0.f;
+        a.a_tile = (int64_t)d.Cb * 4096; a.a_chain = 4096; a.b_tile = (int64_t)d.Cb * 4096; a.b_chain = 4096;
+        a.c_tile_m = 4096; a.c_tile_n = (int64_t)d.Kb * 4096; a.a_ld = a.b_ld = a.c_ld = 64;
+        BRG_REQUIRE((int64_t)d.Kb * d.Nb < (1ll << 31), BRG_EUNSUPPORTED, "brg_fc_fwd: grid too large");
+        if (out_dtype == BRG_BF16) return launch_h64<false, true, false, bf16_t>(a, s, "brg_fc_fwd (bf16, 64-wide blocks) launch");
+        return launch_h64<false, true, false, float>(a, s, "brg_fc_fwd (bf16, 64-wide blocks) launch");
+    }
     if (dtype == BRG_F32 && out_dtype == BRG_F32) return fc_fwd_launch<float, float>(d, X, Wt, bias, act, Y, s);
     if (dtype == BRG_BF16 && out_dtype == BRG_F32) return fc_fwd_launch<bf16_t, float>(d, X, Wt, bias, act, Y, s);
     if (dtype == BRG_BF16 && out_dtype == BRG_BF16) return fc_fwd_launch<bf16_t, bf16_t>(d, X, Wt, bias, act, Y, s);
@@ -408,6 +449,44 @@ static int fc_bwd_impl(const brg_fc_desc_t *desc, brg_dtype_t dtype, const void 
         return launch_g64(a, 64, 1, s, "brg_fc_bwd launch");
     }
     if (dtype == BRG_F32) return fc_bwd_launch<float>(d, dY, Y, X, Wt, relu, relu_in, dX, dWt, dbias, s);
+    if (fc_blocks_64(d) && (!relu || ws) && (int64_t)d.Kb * d.Cb < (1ll << 31) && (int64_t)d.Nb * d.Cb < (1ll << 31)) {
+        // 64-wide bf16 blocks on the bf16 batch-reduce kernel; the ReLU masks are passes of their own, as for
+        // 16-wide blocks (dZ = dY o [Y > 0] into the workspace, the producer's mask on dX in place)
+        if (relu) {
+            rc = launch_fc_mask_bf16(ws, dY, Y, (int64_t)d.N * d.K, s, "brg_fc_bwd (ReLU mask) launch");
+            if (rc) return rc;
+            dY = ws;
+            relu = 0;
+        }
+        if (dX) {   // dX block (nb, cb) [n][c] = sum_kb W(kb, cb) [c][k] (reduction contiguous) * dZ(nb, kb) [n][k]
+            H64Args a = {};
+            a.A = (const bf16_t *)Wt; a.B = (const bf16_t *)dY; a.C = dX; a.act = BRG_ACT_NONE;
+            a.tiles_m = d.Cb; a.tiles_n = d.Nb; a.chain = d.Kb; a.alpha = 1.f; a.beta = 0.f;
+            a.a_tile = 4096; a.a_chain = (int64_t)d.Cb * 4096; a.b_tile = (int64_t)d.Kb * 4096; a.b_chain = 4096;
+            a.c_tile_m = 4096; a.c_tile_n = (int64_t)d.Cb * 4096; a.a_ld = a.b_ld = a.c_ld = 64;
+            rc = launch_h64<true, true, false, bf16_t>(a, s, "brg_fc_bwd (data, bf16, 64-wide blocks) launch");
+            if (rc) return rc;
+            if (relu_in) {
+                rc = launch_fc_mask_bf16(dX, dX, X, (int64_t)d.N * d.C, s, "brg_fc_bwd (producer mask) launch");
+                if (rc) return rc;
+            }
+        }
+        if (dWt) {  // dW block (kb, cb) [c][k] = sum_nb dZ(nb, kb) [n][k] * X(nb, cb) [n][c]: both reductions strided
+            H64Args a = {};
+            a.A = (const bf16_t *)dY; a.B = (const bf16_t *)X; a.C = dWt; a.act = BRG_ACT_NONE;
+            a.tiles_m = d.Kb; a.tiles_n = d.Cb; a.chain = d.Nb; a.alpha = 1.f; a.beta = 0.f;
+            a.a_tile = 4096; a.a_chain = (int64_t)d.Kb * 4096; a.b_tile = 4096; a.b_chain = (int64_t)d.Cb * 4096;
+            a.c_tile_m = (int64_t)d.Cb * 4096; a.c_tile_n = 4096; a.a_ld = a.b_ld = a.c_ld = 64;
+            rc = launch_h64<false, false, false, float>(a, s, "brg_fc_bwd (weights, bf16, 64-wide blocks) launch");
+            if (rc) return rc;
+        }
+        if (dbias) {
+            hipLaunchKernelGGL(fc_dbias_bf16_b64, dim3(d.Kb), dim3(256), 0, s, (const bf16_t *)dY, dbias, d.Nb, d.Kb);
+            rc = check_launch("brg_fc_bwd (bias) launch");
+            if (rc) return rc;
+        }
+        return BRG_OK;
+    }
     if (relu && ws && fc_is_conv1x1(d) && d.bn % 16 == 0) {
         // the masked gradient dZ = dY o [Y > 0] as a pass of its own into the caller's workspace; the tuned
         // kernels below then see an unmasked problem

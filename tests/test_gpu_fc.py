@@ -190,18 +190,19 @@ def test_fc_bf16_16_blocks_full_size_runs_as_1x1_convolution():
     check(db, rb, brg.BF16, "db", out=brg.F32)
 
 
-@pytest.mark.parametrize("N,C,K,bn", [(256, 128, 192, 64), (128, 256, 128, 32), (1024, 1024, 1024, 64)])
-def test_fc_bf16_16_blocks_masked_backward_with_workspace(N, C, K, bn):
-    """bf16, bc = bk = 16, act = RELU and act_in = RELU with a workspace: dZ = dY o [Y > 0] is written to the
+@pytest.mark.parametrize("N,C,K,bn,bc", [(256, 128, 192, 64, 16), (128, 256, 128, 32, 16), (1024, 1024, 1024, 64, 16),
+                                         (256, 128, 192, 64, 64), (128, 320, 64, 64, 64), (1024, 1024, 1024, 64, 64)])
+def test_fc_bf16_16_blocks_masked_backward_with_workspace(N, C, K, bn, bc):
+    """bf16, bc = bk = 16 or 64, act = RELU and act_in = RELU with a workspace: dZ = dY o [Y > 0] is written to the
     workspace by a pass of its own, the tuned kernels run on it, and the producer's mask is applied to dX in place."""
     rng = np.random.default_rng(N + C + K + bn)
-    d = orc.FcShape(N, C, K, bn, 16, 16)
+    d = orc.FcShape(N, C, K, bn, bc, bc)
     X = np.maximum(wl.uniform(rng, d.x_shape), 0)
     W = wl.normal(rng, d.w_shape, (1.0 / C) ** 0.5)
     Y = np.maximum(wl.uniform(rng, d.y_shape), 0)
     dY = wl.uniform(rng, d.y_shape)
     Xs, Ws, Ys, dYs = (as_seen_by_gpu(v, brg.BF16) for v in (X, W, Y, dY))
-    desc = brg.FcDesc(N, C, K, bn, 16, 16)
+    desc = brg.FcDesc(N, C, K, bn, bc, bc)
     dX, dW, db = empty(d.x_shape, brg.BF16), empty(d.w_shape), empty((K,))
     ws = workspace(N * K * 2)
     brg.brg_fc_bwd_chain(desc, brg.BF16, dev(dY, brg.BF16), dev(Y, brg.BF16), dev(X, brg.BF16), dev(W, brg.BF16),
@@ -216,7 +217,7 @@ def test_fc_bf16_16_blocks_masked_backward_with_workspace(N, C, K, bn):
 
 @pytest.mark.parametrize("knob,val", [("BRG_FC_GENERAL", "1"), ("BRG_FC_G64", "64"), ("BRG_FC_G64", "32"), ("BRG_NO_RING", "1"),
                                       ("BRG_FC_G128", "0"), ("BRG_FC_WGT_GENERAL", "1")])
-@pytest.mark.parametrize("dtype,bc", [(brg.F32, 64), (brg.BF16, 16)])
+@pytest.mark.parametrize("dtype,bc", [(brg.F32, 64), (brg.BF16, 16), (brg.BF16, 64)])
 def test_fc_kernel_variants_forced(monkeypatch, knob, val, dtype, bc):
     """Every override that moves a fully connected layer to another kernel: same results."""
     monkeypatch.setenv(knob, val)
