@@ -501,7 +501,7 @@ static ConvTilePlan plan_view_f32(const ConvView &v)
 
 template <int R, int S, int CG, int NPASS> static int conv_tile_f32_view_go(ConvTilePlan &pl, hipStream_t s)
 {
-    auto kern = conv_tile_f32<R, S, 1, CG, NPASS, 1>;
+    auto kern = conv_tile_f32<R, S, 1, CG, NPASS, 3>;
     int rc = allow_big_lds((const void *)kern, pl.smem);
     if (rc) return rc;
     hipLaunchKernelGGL(kern, pl.grid, dim3(256), pl.smem, s, pl.a);

@@ -93,8 +93,9 @@ template <int R, int S, int STR, int CG, int NPASS, int MODE>
 __global__ __launch_bounds__(256, 2) void conv_tile_f32(ConvTileArgs a)
 {
     // MODE 0: forward, weights as stored; 1: backward by data (taps flipped, roles of c and k swapped);
-    // 2: forward with every 16x16 weight block transposed beforehand (reduction index contiguous)
-    constexpr bool BWD = MODE == 1, WVEC = MODE != 0;
+    // 2: forward with every 16x16 weight block transposed beforehand (reduction index contiguous);
+    // 3: backward by data of one parity class of a strided layer (as 1, results placed on every stride-th pixel)
+    constexpr bool BWD = MODE == 1 || MODE == 3, WVEC = MODE != 0, PLACE = MODE == 3;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const float *__restrict__ I = (const float *)a.I;
     const float *__restrict__ Wt = (const float *)a.Wt;
@@ -169,8 +170,8 @@ __global__ __launch_bounds__(256, 2) void conv_tile_f32(ConvTileArgs a)
     };
 
     // ---- weights: block (ob = kb, ib, tap) at Wt + (kb*w_ob + ib*w_ib + tap')*256, where
-    // tap' = tap for the forward pass and wtap[tap] for backward by data (spatially flipped; for the parity
-    // classes of a strided layer also thinned out to the taps of the class).
+    // tap' = tap for the forward pass, TAPS-1-tap (spatially flipped) for backward by data, and wtap[tap] for the
+    // parity classes of a strided layer (flipped and thinned out to the taps of the class).
     // Lane (li, kg) needs, for MFMA step q, the element (row li, reduction index 4*kg + q):
     //   forward : block[c = 4kg+q][k = li]  -> four dwords 16 elements apart (one float4 from a transposed copy)
     //   backward: block[c = li][k = 4kg+q]  -> one aligned float4
@@ -180,11 +181,14 @@ __global__ __launch_bounds__(256, 2) void conv_tile_f32(ConvTileArgs a)
     // the memory counter retires in order, so weight loads queued behind HBM-latency halo loads
     // would stall the first MFMAs that need them.
     float wcur[UNITS][4], wnxt[UNITS][4];
+    int wt[TAPS];                                       // parity classes: the taps of the class, from the table
+#pragma unroll
+    for (int tp = 0; tp < TAPS; ++tp) wt[tp] = PLACE ? a.wtap[tp] : (BWD ? TAPS - 1 - tp : tp);
     auto load_w = [&](int sidx, float (&w)[UNITS][4]) {
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) {
             const int tap = u % TAPS;
-            const float *src = wlane + ((int64_t)(sidx * CG + u / TAPS) * a.w_ib + (BWD ? a.wtap[tap] : tap)) * 256;
+            const float *src = wlane + ((int64_t)(sidx * CG + u / TAPS) * a.w_ib + wt[tap]) * 256;
             if (WVEC) {
                 const float4v v = *(const float4v *)src;
 #pragma unroll
@@ -225,7 +229,12 @@ __global__ __launch_bounds__(256, 2) void conv_tile_f32(ConvTileArgs a)
                 const int n = fdiv(gr, a.P, a.inv_P), oj = gr - n * a.P;
                 const int lrow = n * a.Hv + oj * STR - v_first;
                 bbase[g] = kg * a.plane_bytes + (lrow * a.Wp + (ok ? oi : 0) * STR) * 16;
-                ooff[g] = (ok && kb_ok) ? (((n * a.Kb + kb) * a.Hout + oj * a.osub + a.ooh) * a.Wout + oi * a.osub + a.oow) * 16 + 4 * kg : -1;
+                // (the general placement serves the parity classes of a strided backward pass only: in the other
+                // forms it costs registers that the 3x3 kernels do not have)
+                if (PLACE)
+                    ooff[g] = (ok && kb_ok) ? (((n * a.Kb + kb) * a.Hout + oj * a.osub + a.ooh) * a.Wout + oi * a.osub + a.oow) * 16 + 4 * kg : -1;
+                else
+                    ooff[g] = (ok && kb_ok) ? (((n * a.Kb + kb) * a.P + oj) * a.Q + oi) * 16 + 4 * kg : -1;
             }
         }
 
