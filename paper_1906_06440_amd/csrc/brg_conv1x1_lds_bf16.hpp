@@ -140,9 +140,12 @@ template <bool WTR, int D, int NGW> __global__ __launch_bounds__(256) void conv1
         _Pragma("unroll") for (int g = 0; g < NGW; ++g) FB[g] = *(const bf16x8v *)(sb_ + g * 1024);   \
         __builtin_amdgcn_sched_barrier(0);                                                            \
     }
-#define L_MFMA(FA, FB)                                                                                \
+#define L_MFMA(FA, FB) L_MFMA_PART(FA, FB, 0, NGW)
+// (pixel groups G0 .. G1-1 of a step: the step's matrix instructions are issued in two halves, one on either side
+// of the barrier, so that a wave waits there with matrix work queued)
+#define L_MFMA_PART(FA, FB, G0, G1)                                                                   \
     {                                                                                                 \
-        _Pragma("unroll") for (int g = 0; g < NGW; ++g) _Pragma("unroll") for (int f = 0; f < 4; ++f) \
+        _Pragma("unroll") for (int g = (G0); g < (G1); ++g) _Pragma("unroll") for (int f = 0; f < 4; ++f) \
             acc[f][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(FA[f], FB[g], acc[f][g], 0, 0, 0);    \
         __builtin_amdgcn_sched_barrier(0);                                                            \
     }
@@ -168,9 +171,10 @@ template <bool WTR, int D, int NGW> __global__ __launch_bounds__(256) void conv1
         for (int j = 0; j < D; ++j) {
             L_LOAD(S[j], u + j + D)                    // set j held step u + j, which is in LDS already
             L_WRITE(S[(j + 1) % D], (j + 1) & 1)
+            L_MFMA_PART(fa[j & 1], fb[j & 1], 0, NGW / 2)
             __syncthreads();
             L_READ(fa[(j + 1) & 1], fb[(j + 1) & 1], (j + 1) & 1)
-            L_MFMA(fa[j & 1], fb[j & 1])
+            L_MFMA_PART(fa[j & 1], fb[j & 1], NGW / 2, NGW)
         }
     }
 #pragma unroll
@@ -186,6 +190,7 @@ template <bool WTR, int D, int NGW> __global__ __launch_bounds__(256) void conv1
 #undef L_WRITE
 #undef L_READ
 #undef L_MFMA
+#undef L_MFMA_PART
 
     // epilogue: register r of lane (li, kg) of tile (f, g) is feature 4kg + r of block kb0 + 4wm + f, pixel li
     // of group grp0 + NGW*wn + g
