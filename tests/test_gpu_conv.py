@@ -415,3 +415,44 @@ def test_conv_general_kernel_forced(monkeypatch, N, C, H, K, R, stride, pad, dty
     check(gpu_fwd(d, I, W, dtype, dtype), orc.conv_fwd(d, Is, Ws, out_bf16=bf), dtype, "fwd (general)")
     check(gpu_bwd_data(d, dO, W, dtype, dtype), orc.conv_bwd_data(d, dOs, Ws, out_bf16=bf), dtype, "bwd-data (general)")
     check(gpu_bwd_wgt(d, I, dO, dtype, use_ws=True), orc.conv_bwd_wgt(d, Is, dOs), dtype, "bwd-wgt (general)", brg.F32)
+
+
+# Seeded random shapes: the planners choose between a dozen kernels by thresholds on N, C, K, the image size, the
+# filter and the stride; forty random layers per input type (rectangular images, any multiple of 16 channels up to
+# 192, filters 1..4 with any padding below the filter, stride 1..2, with and without a workspace) go through
+# whatever each call picks, all three passes, against the oracle.
+def _random_layers(seed, count):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        N = int(rng.integers(1, 5))
+        C, K = 16 * int(rng.integers(1, 13)), 16 * int(rng.integers(1, 13))
+        H, W = int(rng.integers(3, 34)), int(rng.integers(3, 34))
+        R, S = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        if rng.random() < 0.6:
+            S = R
+        stride = int(rng.integers(1, 3))
+        pad = int(rng.integers(0, min(R, S)))
+        if H + 2 * pad < R or W + 2 * pad < S:
+            continue
+        out.append((N, C, H, W, K, R, S, stride, pad, bool(rng.random() < 0.7)))
+    return out
+
+
+@pytest.mark.parametrize("dtype", [brg.BF16, brg.F32])
+@pytest.mark.parametrize("chunk", range(4))
+def test_conv_random_layers(dtype, chunk):
+    out = dtype
+    for (N, C, H, W, K, R, S, stride, pad, use_ws) in _random_layers(4242 + chunk, 10):
+        what = "N%d C%d %dx%d K%d %dx%d s%d p%d ws%d" % (N, C, H, W, K, R, S, stride, pad, use_ws)
+        d = orc.ConvShape(N, C, H, W, K, R, S, stride, pad)
+        rng = np.random.default_rng(N * 1000 + C + K + H)
+        I, Wt, dO = wl.uniform(rng, d.i_shape), wl.normal(rng, d.w_shape, (2.0 / (C * R * S)) ** 0.5), wl.uniform(rng, d.o_shape)
+        Is, Ws, dOs = (as_seen_by_gpu(v, dtype) for v in (I, Wt, dO))
+        bias = wl.uniform(rng, (K,))
+        bf = dtype == brg.BF16
+        check(gpu_fwd(d, I, Wt, dtype, out, bias=bias, act=brg.ACT_RELU, use_ws=use_ws),
+              orc.conv_fwd(d, Is, Ws, bias, orc.ACT_RELU, out_bf16=bf), dtype, what + " fwd", out)
+        check(gpu_bwd_data(d, dO, Wt, dtype, out), orc.conv_bwd_data(d, dOs, Ws, out_bf16=bf), dtype, what + " bwd-data", out)
+        check(gpu_bwd_wgt(d, I, dO, dtype, use_ws=use_ws), orc.conv_bwd_wgt(d, Is, dOs), dtype, what + " bwd-wgt", brg.F32,
+              widen=_wgt_widen(d))
