@@ -236,3 +236,35 @@ def test_fc_kernel_variants_forced(monkeypatch, knob, val, dtype, bc):
     check(dX, rX, dtype, "dX")
     check(dW, rW, dtype, "dW", out=brg.F32)
     check(db, rb, dtype, "db", out=brg.F32)
+
+
+# Seeded random layers: block sizes 16, 32, 64 (equal or mixed), one to five blocks per dimension; forward with bias
+# and ReLU, then the backward pass (with the workspace a bf16 layer needs for its masked form) on the GPU's own Y.
+@pytest.mark.parametrize("dtype", [brg.F32, brg.BF16])
+def test_fc_random_layers(dtype):
+    rng = np.random.default_rng(777)
+    for case in range(24):
+        if rng.random() < 0.5:
+            bn = bc = bk = int(rng.choice([16, 64]))
+            if bn == 16:
+                bn = int(rng.choice([16, 32, 64]))
+        else:
+            bn, bc, bk = (int(rng.choice([16, 32, 64])) for _ in range(3))
+        N, C, K = bn * int(rng.integers(1, 6)), bc * int(rng.integers(1, 6)), bk * int(rng.integers(1, 6))
+        what = "N%d C%d K%d blocks %d,%d,%d" % (N, C, K, bn, bc, bk)
+        d = orc.FcShape(N, C, K, bn, bc, bk)
+        X, W = wl.uniform(rng, d.x_shape), wl.normal(rng, d.w_shape, (1.0 / C) ** 0.5)
+        b, dY = wl.normal(rng, (K,), 0.1), wl.uniform(rng, d.y_shape)
+        Xs, Ws, dYs = (as_seen_by_gpu(v, dtype) for v in (X, W, dY))
+        bf = dtype == brg.BF16
+        Y = _fwd(d, X, W, b, brg.ACT_RELU, dtype, dtype)
+        check(Y, orc.fc_fwd(d, Xs, Ws, b, orc.ACT_RELU, bf), dtype, what + " fwd")
+        desc = brg.FcDesc(N, C, K, bn, bc, bk)
+        dX, dW, db = empty(d.x_shape, dtype), empty(d.w_shape), empty((K,))
+        ws = workspace(N * K * 2) if bf else None
+        brg.brg_fc_bwd(desc, dtype, dev(dY, dtype), dev(Y, dtype), dev(X, dtype), dev(W, dtype), brg.ACT_RELU, dX, dW, db, ws)
+        torch.cuda.synchronize()
+        rX, rW, rb = orc.fc_bwd(d, dYs, Y, Xs, Ws, orc.ACT_RELU, dx_bf16=bf)
+        check(host(dX), rX, dtype, what + " dX")
+        check(host(dW), rW, dtype, what + " dW", out=brg.F32)
+        check(host(db), rb, dtype, what + " db", out=brg.F32)

@@ -256,3 +256,32 @@ def test_config4_full_size_bf16():
     d = orc.LstmShape(50, 64, 1024, 1024, 16, 64, 64)
     h, s, g = gpu_lstm(d, x, W4, R4, dtype=brg.BF16)
     _check_bf16_lstm(d, x, W4, R4, None, None, None, h, s, g, "cfg4 bf16")
+
+
+# Seeded random layers: any T, N up to 200, C and K multiples of the block sizes; forward fp32 and bf16 (whatever
+# path the call picks: resident kernels for 64-wide blocks and K a multiple of 64, one launch per step otherwise).
+@pytest.mark.parametrize("dtype", [brg.F32, brg.BF16])
+def test_lstm_random_layers(dtype):
+    rng = np.random.default_rng(99)
+    for case in range(10):
+        if rng.random() < 0.6:
+            bc = bk = 64
+        else:
+            bc, bk = int(rng.choice([8, 16, 32])), int(rng.choice([8, 16, 32]))
+        T, N = int(rng.integers(1, 8)), int(rng.integers(1, 200))
+        C, K = bc * int(rng.integers(1, 5)), bk * int(rng.integers(1, 6))
+        x, W4, R4, b4 = wl.cfg4_lstm(T, N, C, K, bc, bk, with_bias=True, seed_extra=case)
+        W4 *= 4.0
+        R4 *= 4.0
+        h0, s0 = wl.uniform(rng, (N, K), -0.5, 0.5), wl.uniform(rng, (N, K), -0.5, 0.5)
+        x, W4, R4, h0 = (as_seen_by_gpu(v, dtype) for v in (x, W4, R4, h0))     # (the oracle is fed what the GPU is fed)
+        d = orc.LstmShape(T, N, C, K, 16, bc, bk)
+        h, s, g = gpu_lstm(d, x, W4, R4, b4=b4, h0=h0, s0=s0, dtype=dtype)
+        what = "T%d N%d C%d K%d blocks %d,%d" % (T, N, C, K, bc, bk)
+        if dtype == brg.BF16:
+            _check_bf16_lstm(d, x, W4, R4, b4, h0, s0, h, s, g, what)
+        else:
+            rh, rs, rg = orc.lstm_fwd(d, x, W4, R4, b4, h0, s0)
+            check(h, rh, brg.F32, what + " h")
+            check(s, rs, brg.F32, what + " s")
+            check(g, rg, brg.F32, what + " gates")
