@@ -176,3 +176,33 @@ def test_bf16_strided_blocks_on_the_bf16_matrix_instruction(out, m, n, count, ld
         want = _oracle_strided(A, B, m, n, k, lda, ldb, ldc, count, sa, sb, brg.BF16, out, alpha, beta, C0, b, act)
         check(got[:, :m], want[:, :m], brg.BF16, f"bf16 {m}x{n}x{k}x{count}", out)
         assert np.array_equal(got[:, m:], as_seen_by_gpu(C0, out)[:, m:])
+
+
+# Seeded random calls of the stride form: any m, n, k up to 150 (half of them multiples of 64, where the tuned
+# kernels apply), padded leading dimensions, chains of 0..20 blocks, strides that are zero, equal to a block or
+# larger, random alpha / beta / bias, none or ReLU (the saturating activations have their own test with pre-activations
+# of order one: behind sums of order ten the absolute rounding error of the sum exceeds a bound taken from outputs below one).
+@pytest.mark.parametrize("dtype,out", [(brg.F32, brg.F32), (brg.BF16, brg.F32), (brg.BF16, brg.BF16)])
+def test_random_strided_calls(dtype, out):
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        if rng.random() < 0.5:
+            m, n, k = 64 * int(rng.integers(1, 3)), 64 * int(rng.integers(1, 3)), 64
+        else:
+            m, n, k = (int(rng.integers(1, 151)) for _ in range(3))
+        count = int(rng.integers(0, 21))
+        lda, ldb, ldc = m + 8 * int(rng.integers(0, 3)), k + 8 * int(rng.integers(0, 3)), m + 8 * int(rng.integers(0, 3))
+        sa = int(rng.choice([0, lda * k, lda * k + 16]))
+        sb = int(rng.choice([0, ldb * n, ldb * n + 24]))
+        A = 2 * rng.random(max(1, count) * (lda * k + 16), dtype=np.float32) - 1
+        B = 2 * rng.random(max(1, count) * (ldb * n + 24), dtype=np.float32) - 1
+        C0 = 2 * rng.random((n, ldc), dtype=np.float32) - 1
+        bias = (2 * rng.random(m, dtype=np.float32) - 1) if rng.random() < 0.5 else None
+        alpha, beta = float(rng.choice([1.0, 0.5, -2.0])), float(rng.choice([0.0, 1.0, -0.5]))
+        act = int(rng.choice([brg.ACT_NONE, brg.ACT_RELU]))
+        what = "case %d: %dx%dx%d count %d ld %d,%d,%d strides %d,%d alpha %g beta %g act %d" % (
+            case, m, n, k, count, lda, ldb, ldc, sa, sb, alpha, beta, act)
+        got = _run_strided(A, B, m, n, k, lda, ldb, ldc, count, sa, sb, dtype, out, alpha, beta, C0, bias, act)
+        want = _oracle_strided(A, B, m, n, k, lda, ldb, ldc, count, sa, sb, dtype, out, alpha, beta, C0, bias, act)
+        check(got[:, :m], want[:, :m], dtype, what, out)
+        assert np.array_equal(got[:, m:], as_seen_by_gpu(C0, out)[:, m:]), what
