@@ -142,7 +142,7 @@ int brg_gemm_strided(brg_dtype_t dtype, brg_dtype_t out_dtype, int64_t m, int64_
  *                     to I (the paper's "dual convolution"); input pixels that
  *                     no tap reads are written as 0.
  *  brg_conv_bwd_wgt   dWt (fp32, layout of Wt) = sum_{n,oj,oi} dO * I.  Tuned for bf16 layers (and fp32
- *                     ones except the strided 3x3 and the bc = 4 layer) with 1x1
+ *                     ones except the bc = 4 layer) with 1x1
  *                     filters (stride 1 or 2, no padding), 3x3 filters (padding 1, stride 1 or 2) and
  *                     the bc = 4 layer (which has no other path) when given the workspace of
  *                     brg_conv_bwd_wgt_ws_bytes; general kernel otherwise.

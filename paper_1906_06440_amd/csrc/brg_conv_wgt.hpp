@@ -782,6 +782,112 @@ __global__ __launch_bounds__(256) void conv_wgt3x3_f32(ConvWgt3Args a)
         }
 }
 
+// 3x3, stride 2, padding 1 in fp32: the four phase planes of conv_wgt3x3s2_bf16 (64 bytes per pixel), windows of
+// 32 + Q + 1 plane pixels, no transposition (the operand of 16x16x4 is one element per lane).  A workgroup owns one
+// channel block x 4 feature blocks (wave: one feature block x 9 taps); the taps with a column shift of -1 are masked
+// where q = 0.
+__global__ __launch_bounds__(256) void conv_wgt3x3s2_f32(ConvWgt2Args a)
+{
+    __shared__ __attribute__((aligned(16))) float win[2][4][CW2_WINMAX * 16];   // [buffer][plane 2a+b][window row x 16]
+    __shared__ __attribute__((aligned(16))) float slab[2][4][32 * 16];          // [buffer][feature block][32 pixels x 16]
+    const float *gI = (const float *)a.I, *gO = (const float *)a.dO;
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int li = lane & 15, kg = lane >> 4;
+    const int cb0 = blockIdx.x, kb0 = blockIdx.y * 4;
+    const int s_begin = blockIdx.z * a.steps_per_split;
+    const int s_end = min(a.steps_total, s_begin + a.steps_per_split);
+    const int H = a.H, W = a.W, Q = a.Q, PQ = a.P * a.Q, HWin = a.H * a.W;
+    const int WINS = 32 + Q + 1;
+
+    // window pieces e = t + 256 j < 4 * WINS * 4: plane e / (4 WINS), window row (e / 4) % WINS, quarter e % 4
+    constexpr int NP = (4 * CW2_WINMAX * 4 + 255) / 256;                // 4
+    int p_row[NP], p_ab[NP];
+#pragma unroll
+    for (int j = 0; j < NP; ++j) {
+        const int e = t + 256 * j;
+        const int pl = e / (4 * WINS);
+        p_ab[j] = pl & 3;
+        p_row[j] = pl < 4 ? (e - pl * 4 * WINS) >> 2 : -1;
+    }
+    float4v dstage[2], wstage[NP];
+    auto load_step = [&](int s) {
+        const int n = s / a.steps_per_img;
+        const int pix0 = (s - n * a.steps_per_img) * 32;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int e = t + 256 * j, kb = e >> 7, pix = pix0 + ((e & 127) >> 2);
+            float4v v = {0.f, 0.f, 0.f, 0.f};
+            if (pix < PQ) v = *(const float4v *)(gO + (((int64_t)n * a.Kb + kb0 + kb) * PQ + pix) * 16 + (e & 3) * 4);
+            dstage[j] = v;
+        }
+#pragma unroll
+        for (int j = 0; j < NP; ++j) {
+            const int jp = pix0 - (Q + 1) + p_row[j];                   // flattened plane pixel of this window row
+            float4v v = {0.f, 0.f, 0.f, 0.f};
+            if (p_row[j] >= 0 && jp >= 0) {
+                const int y = (int)(((float)jp + 0.5f) * a.inv_Q), x = jp - y * Q;
+                const int iy = 2 * y + (p_ab[j] >> 1), ix = 2 * x + (p_ab[j] & 1);
+                if (iy < H && ix < W) v = *(const float4v *)(gI + (((int64_t)n * a.Cb + cb0) * HWin + iy * W + ix) * 16 + (t & 3) * 4);
+            }
+            wstage[j] = v;
+        }
+    };
+    auto store_step = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int e = t + 256 * j;
+            *(float4v *)(&slab[buf][e >> 7][(e & 127) * 4]) = dstage[j];
+        }
+#pragma unroll
+        for (int j = 0; j < NP; ++j)
+            if (p_row[j] >= 0) *(float4v *)(&win[buf][p_ab[j]][p_row[j] * 16 + (t & 3) * 4]) = wstage[j];
+    };
+
+    float4v acc[9];
+#pragma unroll
+    for (int tp = 0; tp < 9; ++tp) acc[tp] = float4v{0.f, 0.f, 0.f, 0.f};
+
+    if (s_begin < s_end) {
+        load_step(s_begin);
+        store_step(0);
+    }
+    __syncthreads();
+    for (int s = s_begin; s < s_end; ++s) {
+        const int buf = (s - s_begin) & 1;
+        if (s + 1 < s_end) load_step(s + 1);
+        const int n = s / a.steps_per_img;
+        int q = ((s - n * a.steps_per_img) * 32 + kg) % Q;             // column of this lane's output pixel in k step 0
+#pragma unroll
+        for (int j4 = 0; j4 < 8; ++j4) {
+            const int prow = 4 * j4 + kg;
+            const float fb = slab[buf][wave][prow * 16 + li];
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int sx = 0; sx < 3; ++sx) {
+                    const int pa = r == 1 ? 0 : 1, pb = sx == 1 ? 0 : 1;             // phase plane
+                    const int toff = (r == 0 ? 0 : Q) + (sx == 0 ? 0 : 1);          // window row of shift (dy, dx)
+                    float fa = win[buf][2 * pa + pb][(prow + toff) * 16 + li];
+                    if (sx == 0 && q == 0) fa = 0.f;
+                    acc[3 * r + sx] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa, fb, acc[3 * r + sx], 0, 0, 0);
+                }
+            q += 4;
+            while (q >= Q) q -= Q;
+        }
+        if (s + 1 < s_end) store_step(buf ^ 1);
+        __syncthreads();
+    }
+
+    float *out = a.out + (int64_t)blockIdx.z * a.Kb * a.Cb * 9 * 256;
+#pragma unroll
+    for (int tp = 0; tp < 9; ++tp) {
+        float *blk = out + (((int64_t)(kb0 + wave) * a.Cb + cb0) * 9 + tp) * 256;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) blk[(4 * kg + rr) * 16 + li] = acc[tp][rr];
+    }
+}
+
 // dWt = sum of the partial sums of the ranges.  A workgroup owns 64 consecutive float4 of dWt (n4 is a
 // multiple of 64); wave w adds the ranges w, w + 4, ... in order with fully coalesced loads, then the four
 // partial sums are added in a fixed order through LDS, so the result does not depend on timing.
@@ -817,7 +923,7 @@ static ConvWgtPlan conv_wgt_plan(int64_t N, int64_t C, int64_t H, int64_t W, int
 {
     ConvWgtPlan p = {};
     p.f32 = f32;
-    if (f32 && (bc != 16 || (R == 3 && sh != 1))) return p;         // fp32: 1x1 (stride 1, 2) and 3x3 stride 1 only
+    if (f32 && bc != 16) return p;
     const bool is1 = R == 1 && S == 1 && ph == 0 && pw == 0 && sh == sw && (sh == 1 || sh == 2);
     const bool is3 = R == 3 && S == 3 && ph == 1 && pw == 1 && W >= 3 && W <= 63 && sh == 1 && sw == 1;
     const bool is3s2 = R == 3 && S == 3 && ph == 1 && pw == 1 && sh == 2 && sw == 2 && W >= 3 && (W - 1) / 2 + 1 <= 31;
@@ -845,7 +951,7 @@ static ConvWgtPlan conv_wgt_plan(int64_t N, int64_t C, int64_t H, int64_t W, int
     p.taps = is1 ? 1 : 9;
     p.s2 = is3s2;
     p.WT = (!f32 && is1 && Cb % 8 == 0 && Kb % 8 == 0 && (Cb / 8) * (Kb / 8) >= 16) ? 4 : 2;
-    const int64_t nb = (is3s2 || (f32 && is3)) ? (Cb / 2) * (Kb / 4) : (Cb / (2 * p.WT)) * (Kb / (2 * p.WT));
+    const int64_t nb = (f32 && is3s2) ? Cb * (Kb / 4) : (is3s2 || (f32 && is3)) ? (Cb / 2) * (Kb / 4) : (Cb / (2 * p.WT)) * (Kb / (2 * p.WT));
     p.ps = 1;
     if (is1 && !f32) {
         p.ps = 2;
@@ -895,6 +1001,13 @@ static int conv_wgt_bf16_launch(const ConvWgtPlan &p, int N, int Cb, int Kb, int
             a.Q = (W - 1) / stride + 1; a.HW = ((H - 1) / stride + 1) * a.Q; a.HWin = H * W; a.Win = W;
             a.steps_per_img = p.steps_per_img; a.steps_total = p.steps_total; a.steps_per_split = p.steps_per_split;
             hipLaunchKernelGGL(conv_wgt1x1_f32, dim3(Cb / 4, Kb / 4, p.nsplit), dim3(256), 0, s, a);
+        } else if (p.s2) {
+            ConvWgt2Args a = {};
+            a.I = (const bf16_t *)I; a.dO = (const bf16_t *)dO; a.out = out;
+            a.N = N; a.Cb = Cb; a.Kb = Kb; a.H = H; a.W = W; a.P = (H - 1) / 2 + 1; a.Q = (W - 1) / 2 + 1;
+            a.inv_Q = 1.0f / (float)a.Q;
+            a.steps_per_img = p.steps_per_img; a.steps_total = p.steps_total; a.steps_per_split = p.steps_per_split;
+            hipLaunchKernelGGL(conv_wgt3x3s2_f32, dim3(Cb, Kb / 4, p.nsplit), dim3(256), 0, s, a);
         } else {
             ConvWgt3Args a = {};
             a.I = (const bf16_t *)I; a.dO = (const bf16_t *)dO; a.out = out;

@@ -348,7 +348,7 @@ def test_resnet50_layers_small_minibatch_bf16(N):
     (4, 64, 14, 64, 3, 2), (2, 64, 28, 128, 3, 2), (2, 128, 56, 64, 3, 2), (3, 64, 13, 64, 3, 2), (1, 64, 15, 64, 3, 2)])
 @pytest.mark.parametrize("dtype", [brg.BF16, brg.F32])
 def test_conv_bwd_wgt_bf16_tuned(N, C, H, K, R, stride, dtype):
-    """(fp32: the 1x1 and the stride-1 3x3 shapes run on the fp32 forms of the kernels, the others on the general one)"""
+    """(fp32: the same shapes on the fp32 forms of the kernels)"""
     pad = (R - 1) // 2
     I, W, dO = wl.conv_tensors(N, C, H, K, R, stride, pad, cfg_index=5, seed_extra=N + H, want_dO=True)
     d = orc.ConvShape(N, C, H, H, K, R, R, stride, pad)
