@@ -57,7 +57,9 @@ const char *brg_version(void);
  * the planner would not choose by itself; they exist so that every variant can be parity-tested and timed.
  * The environment is read once, at the first call into the library; brg_tuning_reload() reads it again
  * (not safe against calls running at the same time on other threads).  Results never depend on them
- * beyond rounding order.  Presence alone switches the ones marked (flag); the others take a number.
+ * beyond rounding order.  A workspace size query and the call it serves must see the SAME overrides (the planner
+ * that sizes the workspace is the one that uses it).  Presence alone switches the ones marked (flag); the others
+ * take a number.
  *   BRG_GEMM_GENERAL (flag)   brg_gemm*: always the general tile kernel
  *   BRG_NO_RING (flag)        64-cubed fp32 blocks: the double-buffered kernel instead of the four-stage ring
  *   BRG_FC_GENERAL (flag), BRG_FC_WGT_GENERAL (flag), BRG_FC_G64 = 64|32, BRG_FC_G128 = 0|1
