@@ -41,12 +41,12 @@ def kernel_sources_sha(files):
     return h.hexdigest()[:16]
 
 
-def measured_traffic(workload):
+def measured_traffic(workload, profiles_dir=None):
     """(bytes per step, source) from the committed profile of this workload, or (None, reason)."""
     name = TRAFFIC_PROFILE.get(workload)
     if not name:
         return None, "no counter profile for this workload"
-    path = os.path.join(ROOT, "profiles", name)
+    path = os.path.join(profiles_dir or os.path.join(ROOT, "profiles"), name)
     try:
         for line in open(path):
             if line.startswith("TRAFFIC "):
